@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the S2O prefill-attention hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch that is already resident in
+HBM: s2o_plan (ranking: pooling, scores, both Argsorts) followed by s2o_attention (dense
+intra-segment window + ranked prefix walk with early stopping) at one threshold.  Prints
+ONE JSON line (see the keys below); `value` is the time of that whole step in ms/layer.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+
+def tile_flops(w, computed, skipped):
+    """Algorithmic FLOPs of one attention launch on computed blocks: Pass-1's causal
+    triangle of tiles + every folded-in prefix tile (QK^T and PV), + QK^T only for
+    triggering tiles that were discarded."""
+    from oracle.s2o_oracle import pass1_tiles, prefix_tiles  # bookkeeping helpers only
+    full = 4 * w.BM * w.BN * w.D
+    t1 = pass1_tiles(w.L, w.S, w.BM) * w.Z * w.H
+    total = prefix_tiles(w.L, w.S, w.BM, w.BN)[None, None]
+    trig = (total - computed - skipped).sum()
+    return float((t1 + computed.sum()) * full + trig * (full // 2)), int(trig)
+
+
+def plan_bytes(w):
+    """Algorithmic HBM bytes of one plan launch: read Q and K once, write both maps."""
+    P = w.S * w.N * (w.N - 1) // 2
+    return (w.Z * w.H * w.L * w.D * 2 + w.Z * w.Hkv * w.L * w.D * 2
+            + w.Z * w.H * P * 4 + w.Z * w.H * w.L * 4)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="llama128k")
+    ap.add_argument("--tau", type=float, default=5e-3)
+    ap.add_argument("--sweep", action="store_true", help="also time every tau of the workload")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mse", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2602_22575_amd as s2o
+    from paper_2602_22575_amd import inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    s2o.load_library()
+    dev = torch.device("cuda:0")
+    w = inputs.workload(args.workload)
+    t0 = time.time()
+    Qb, Kb, Vb = inputs.make_qkv(w)
+    t_gen = time.time() - t0
+    to_dev = lambda b: torch.from_numpy(b.view(np.int16)).to(dev).view(torch.bfloat16)
+    Qd, Kd, Vd = to_dev(Qb), to_dev(Kb), to_dev(Vb)
+    params = s2o.make_params(w.Z, w.H, w.Hkv, w.L, w.D, w.S, w.BM, w.BN)
+    sizes = s2o.s2o_plan_sizes(params)
+    scratch = torch.empty(sizes["scratch"], dtype=torch.uint8, device=dev)
+    O = torch.empty((w.Z, w.H, w.L, w.D), dtype=torch.bfloat16, device=dev)
+    comp = torch.empty((w.Z, w.H, w.L // w.BM), dtype=torch.int32, device=dev)
+    skip = torch.empty_like(comp)
+
+    def step(tau):
+        plan = s2o.s2o_plan(Qd, Kd, params, want_scores=False, scratch=scratch)
+        s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau, O=O, computed=comp, skipped=skip)
+        return plan
+
+    def timed(fn, iters):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+        ev[0].record()
+        for i in range(iters):
+            fn()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        return [ev[i].elapsed_time(ev[i + 1]) for i in range(iters)]
+
+    for _ in range(args.warmup):
+        step(args.tau)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        plan = step(args.tau)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-stage device time with events on the launch stream
+    plan_ms = float(np.mean(timed(lambda: s2o.s2o_plan(Qd, Kd, params, want_scores=False, scratch=scratch),
+                                  max(args.steps, 3))))
+    attn_fn = lambda tau: s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau, O=O,
+                                            computed=comp, skipped=skip)
+    attn_ms = float(np.mean(timed(lambda: attn_fn(args.tau), max(args.steps, 3))))
+    c, s = comp.cpu().numpy(), skip.cpu().numpy()
+    flops, trig = tile_flops(w, c, s)
+    from oracle.s2o_oracle import density as density_of
+    dens = float(density_of(s, w.L, w.S, w.BM, w.BN).mean())
+    tflops = flops / (attn_ms * 1e-3) / 1e12
+
+    extra = {}
+    if not args.no_mse:
+        O_tau = O.float()
+        Od = torch.empty_like(O)
+        dense_ms = float(np.mean(timed(lambda: s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm,
+                                                                 0.0, O=Od), 2)))
+        ref = Od.float()
+        per_head = ((O_tau - ref) ** 2).mean(dim=(0, 2, 3))
+        extra["mse_vs_dense"] = float(per_head.mean())
+        extra["rel_mse_vs_dense"] = float(((O_tau - ref) ** 2).sum() / (ref ** 2).sum())
+        extra["dense_tau0_ms"] = dense_ms
+        extra["dense_tau0_tflops"] = 4.0 * w.BM * w.BN * w.D * (w.L // w.BM) * (w.L // w.BM + 1) / 2 * w.Z * w.H \
+            / (dense_ms * 1e-3) / 1e12
+        del O_tau, ref, Od
+    if args.sweep:
+        sweep = []
+        for tau in w.taus:
+            ms = float(np.mean(timed(lambda: attn_fn(tau), 3)))
+            cc, ss = comp.cpu().numpy(), skip.cpu().numpy()
+            f, _ = tile_flops(w, cc, ss)
+            sweep.append(dict(tau=tau, attn_ms=ms, density=float(density_of(ss, w.L, w.S, w.BM, w.BN).mean()),
+                              tflops=f / (ms * 1e-3) / 1e12))
+        extra["tau_sweep"] = sweep
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, Qb, Kb, Vb, plan, args.tau, float((w.N * (w.N - 1) // 2) * (w.S // w.BN)
+                                                                 * (w.S // w.BM) * w.Z * w.H - s.sum()))
+
+    out = {
+        "metric": "128K prefill attn ms/layer (plan + sparse attention), TFLOP/s on computed blocks, MSE vs dense at sparsity",
+        "value": ms_per_step, "unit": "ms/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: Z={w.Z} H={w.H} Hkv={w.Hkv} L={w.L} D={w.D} S={w.S} "
+                               f"tiles {w.BM}x{w.BN} tau={args.tau} stop_mode=0 seed={w.seed}"},
+        "plan_ms": plan_ms, "attn_ms": attn_ms, "density": dens, "sparsity": 1 - dens,
+        "tflops_on_computed_blocks": tflops, "triggering_tiles": trig,
+        "plan_algorithmic_GBps": plan_bytes(w) / (plan_ms * 1e-3) / 1e9,
+        "plan_frac_of_hbm_peak": plan_bytes(w) / (plan_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "input_generation_s": t_gen,
+        "roofline": {"bound": "mfma", "kernel": "s2o_attention_kernel", "achieved": tflops,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
+                     "traffic": None},
+        "cpu_baseline": cpu,
+    }
+    out.update(extra)
+    print(json.dumps(out))
+
+
+def cpu_baseline(w, Qb, Kb, Vb, plan, tau, issued_tiles_gpu):
+    """The fp64 oracle as it stands, timed on this machine's host cores on a bounded sample of
+    the same workload: Alg. 2 + Alg. 3 for a few (head, segment) pairs with the GPU's maps;
+    the per-issued-tile time is scaled to the whole layer."""
+    from oracle import s2o_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    heads = [0, w.H - 1] if w.H > 1 else [0]
+    segs = sorted({min(1, w.N - 1), w.N // 3}) if w.N > 2 else list(range(w.N))
+    G = w.G
+    qp = plan.q_perm.cpu().numpy()
+    kp = plan.kv_perm.cpu().numpy()
+    t0 = time.perf_counter()
+    tiles = 0
+    for h in heads:
+        g = h // G
+        Q1 = orc.bf16_bits_to_f64(Qb[:, h:h + 1])
+        K1 = orc.bf16_bits_to_f64(Kb[:, g:g + 1])
+        V1 = orc.bf16_bits_to_f64(Vb[:, g:g + 1])
+        _, c, s = orc.attention(Q1, K1, V1, qp[:, h:h + 1], kp[:, h:h + 1], w.S, w.BM, w.BN, tau,
+                                segments=segs)
+        tj = w.S // w.BM
+        for n in segs:
+            tiles += int((n * (w.S // w.BN) - s[0, 0, n * tj:(n + 1) * tj]).sum()) + orc.pass1_tiles(w.S, w.S, w.BM)
+    dt = time.perf_counter() - t0
+    total_tiles = issued_tiles_gpu + orc.pass1_tiles(w.L, w.S, w.BM) * w.Z * w.H
+    return {"value": dt / max(tiles, 1) * total_tiles * 1e3, "unit": "ms/layer (extrapolated from the sample)",
+            "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle attention (Alg. 2+3, fp64 numpy) on heads {heads} x segments {segs}: "
+                      f"{tiles} tiles in {dt:.1f} s, scaled by issued tiles to the full layer; plan excluded"}
+
+
+if __name__ == "__main__":
+    main()

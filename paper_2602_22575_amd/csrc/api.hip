@@ -1,0 +1,166 @@
+// Host side of the S2O C ABI (declared in include/s2o.h): argument validation, size
+// queries and kernel launches.  Nothing here allocates device memory or synchronises.
+#include <math.h>
+#include <string.h>
+
+#include "../../include/s2o.h"
+#include "s2o_internal.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+  g_last_hip_error = (int)e;
+  return S2O_EHIP;
+}
+
+struct Shape {
+  int Z, H, Hkv, L, D, S, N;
+  int64_t qs[3], ks[3], vs[3], os[3];
+};
+
+bool fill_strides(const int64_t in[3], int64_t out[3], int heads, int L, int D) {
+  if (in[0] == 0 && in[1] == 0 && in[2] == 0) {
+    out[2] = D;
+    out[1] = (int64_t)L * D;
+    out[0] = (int64_t)heads * L * D;
+    return true;
+  }
+  for (int i = 0; i < 3; ++i) {
+    if (in[i] < 0 || (in[i] % 8) != 0) return false;   // 16-byte aligned rows
+    out[i] = in[i];
+  }
+  return out[2] >= D;
+}
+
+int check_params(const s2o_params* p, Shape* s) {
+  if (!p) return S2O_EINVAL;
+  if (p->struct_size != (int32_t)sizeof(s2o_params)) return S2O_EINVAL;
+  if (p->batch <= 0 || p->q_heads <= 0 || p->kv_heads <= 0 || p->seq_len <= 0 || p->seg_len <= 0)
+    return S2O_EINVAL;
+  if (p->q_heads % p->kv_heads != 0) return S2O_EINVAL;
+  if (p->seq_len % p->seg_len != 0) return S2O_EINVAL;
+  if (p->use_q_perm != 0 && p->use_q_perm != 1) return S2O_EINVAL;
+  if (p->stop_mode != 0 && p->stop_mode != 1) return S2O_EINVAL;
+  if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) return S2O_EINVAL;
+  if (p->head_dim != 128) return S2O_EUNSUPPORTED;
+  if (p->block_m != 64 || p->block_n != 64) return S2O_EUNSUPPORTED;
+  if (p->seg_len % 64 != 0 || p->seg_len > 8192) return S2O_EUNSUPPORTED;
+  if ((int64_t)p->batch * p->q_heads * (p->seq_len / p->seg_len) > (1 << 24)) return S2O_EUNSUPPORTED;
+  s->Z = p->batch; s->H = p->q_heads; s->Hkv = p->kv_heads; s->L = p->seq_len;
+  s->D = p->head_dim; s->S = p->seg_len; s->N = p->seq_len / p->seg_len;
+  if (!fill_strides(p->q_stride, s->qs, s->H, s->L, s->D)) return S2O_EINVAL;
+  if (!fill_strides(p->k_stride, s->ks, s->Hkv, s->L, s->D)) return S2O_EINVAL;
+  if (!fill_strides(p->v_stride, s->vs, s->Hkv, s->L, s->D)) return S2O_EINVAL;
+  if (!fill_strides(p->o_stride, s->os, s->H, s->L, s->D)) return S2O_EINVAL;
+  return S2O_OK;
+}
+
+bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+int s2o_version(void) { return S2O_VERSION; }
+
+const char* s2o_strerror(int code) {
+  switch (code) {
+    case S2O_OK: return "ok";
+    case S2O_EINVAL: return "invalid argument";
+    case S2O_EUNSUPPORTED: return "unsupported configuration (need D=128, 64x64 tiles, S%64==0, S<=8192)";
+    case S2O_ESCRATCH: return "scratch buffer missing, misaligned or too small";
+    case S2O_EHIP: return "HIP runtime error (see s2o_last_hip_error)";
+    default: return "unknown error code";
+  }
+}
+
+int s2o_last_hip_error(void) { return g_last_hip_error; }
+
+int s2o_plan_sizes(const s2o_params* params, size_t* q_perm_bytes, size_t* kv_perm_bytes,
+                   size_t* s_q_bytes, size_t* s_k_bytes, size_t* q_mean_bytes,
+                   size_t* k_guide_bytes, size_t* scratch_bytes) {
+  Shape s;
+  const int rc = check_params(params, &s);
+  if (rc != S2O_OK) return rc;
+  const size_t zh = (size_t)s.Z * s.H;
+  const size_t P = (size_t)s2o::kv_row_offset(s.N, s.S);
+  if (q_perm_bytes) *q_perm_bytes = zh * s.L * 4;
+  if (kv_perm_bytes) *kv_perm_bytes = zh * P * 4;
+  if (s_q_bytes) *s_q_bytes = zh * s.L * 4;
+  if (s_k_bytes) *s_k_bytes = zh * P * 4;
+  if (q_mean_bytes) *q_mean_bytes = zh * s.N * s.D * 4;
+  if (k_guide_bytes) *k_guide_bytes = (size_t)s.Z * s.Hkv * s.D * 4;
+  if (scratch_bytes) *scratch_bytes = s2o::plan_scratch_bytes(s.Z, s.H, s.Hkv, s.L, s.S);
+  return S2O_OK;
+}
+
+int s2o_plan(const void* Q, const void* K, const s2o_params* params, const s2o_plan_out* out,
+             void* scratch, size_t scratch_bytes, void* stream) {
+  Shape s;
+  const int rc = check_params(params, &s);
+  if (rc != S2O_OK) return rc;
+  if (!Q || !K || !out || !out->q_perm) return S2O_EINVAL;
+  if (s.N > 1 && !out->kv_perm) return S2O_EINVAL;
+  if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(out->q_perm, 16) ||
+      misaligned(out->kv_perm, 16))
+    return S2O_EINVAL;
+  const size_t need = s2o::plan_scratch_bytes(s.Z, s.H, s.Hkv, s.L, s.S);
+  if (!scratch || misaligned(scratch, 256) || scratch_bytes < need) return S2O_ESCRATCH;
+
+  s2o::PlanArgs a;
+  memset(&a, 0, sizeof(a));
+  a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K;
+  a.q_perm = out->q_perm; a.kv_perm = out->kv_perm;
+  a.s_q = out->s_q; a.s_k = out->s_k; a.q_mean = out->q_mean; a.k_guide = out->k_guide;
+  a.Z = s.Z; a.H = s.H; a.Hkv = s.Hkv; a.L = s.L; a.S = s.S; a.N = s.N;
+  for (int i = 0; i < 3; ++i) { a.qs[i] = s.qs[i]; a.ks[i] = s.ks[i]; }
+  a.scratch = scratch; a.scratch_bytes = scratch_bytes;
+  const hipError_t e = s2o::launch_plan(a, (hipStream_t)stream);
+  return e == hipSuccess ? S2O_OK : hip_fail(e);
+}
+
+int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* scratch_bytes) {
+  Shape s;
+  const int rc = check_params(params, &s);
+  if (rc != S2O_OK) return rc;
+  if (counts_bytes) *counts_bytes = (size_t)s.Z * s.H * (s.L / params->block_m) * 4;
+  if (scratch_bytes) *scratch_bytes = 0;   // Pass-1 state stays in registers
+  return S2O_OK;
+}
+
+int s2o_attention(const void* Q, const void* K, const void* V, const s2o_params* params,
+                  const int32_t* q_perm, const int32_t* kv_perm, float tau, void* O,
+                  int32_t* computed, int32_t* skipped, void* scratch, size_t scratch_bytes,
+                  void* stream) {
+  (void)scratch; (void)scratch_bytes;
+  Shape s;
+  const int rc = check_params(params, &s);
+  if (rc != S2O_OK) return rc;
+  if (!Q || !K || !V || !O) return S2O_EINVAL;
+  if (params->use_q_perm && !q_perm) return S2O_EINVAL;
+  if (s.N > 1 && !kv_perm) return S2O_EINVAL;
+  if (tau != tau) return S2O_EINVAL;
+  if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(O, 16) ||
+      misaligned(kv_perm, 16))
+    return S2O_EINVAL;
+
+  s2o::AttnArgs a;
+  memset(&a, 0, sizeof(a));
+  a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
+  a.O = (uint16_t*)O;
+  a.q_perm = q_perm; a.kv_perm = kv_perm; a.computed = computed; a.skipped = skipped;
+  a.Z = s.Z; a.H = s.H; a.Hkv = s.Hkv; a.L = s.L; a.S = s.S; a.N = s.N;
+  a.use_q_perm = params->use_q_perm; a.stop_mode = params->stop_mode;
+  a.tau = tau;
+  const float scale = params->softmax_scale > 0.f ? params->softmax_scale : 1.0f / sqrtf((float)s.D);
+  a.scale_log2e = scale * 1.4426950408889634f;
+  for (int i = 0; i < 3; ++i) {
+    a.qs[i] = s.qs[i]; a.ks[i] = s.ks[i]; a.vs[i] = s.vs[i]; a.os[i] = s.os[i];
+  }
+  const hipError_t e = s2o::launch_attention(a, (hipStream_t)stream);
+  return e == hipSuccess ? S2O_OK : hip_fail(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,46 @@
+// Internal declarations shared by the host API and the gfx950 kernels of the S2O library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace s2o {
+
+// Packed start of prefix row n (n >= 1) inside one head's KV_perm / s_K array.
+__host__ __device__ inline int64_t kv_row_offset(int64_t n, int64_t S) { return S * n * (n - 1) / 2; }
+
+struct AttnArgs {
+  const uint16_t* Q;
+  const uint16_t* K;
+  const uint16_t* V;
+  uint16_t* O;
+  const int32_t* q_perm;
+  const int32_t* kv_perm;
+  int32_t* computed;
+  int32_t* skipped;
+  int Z, H, Hkv, L, S, N;
+  int use_q_perm, stop_mode;
+  float tau;
+  float scale_log2e;  // softmax_scale * log2(e): logits are kept in base-2 units
+  int64_t qs[3], ks[3], vs[3], os[3];
+};
+
+struct PlanArgs {
+  const uint16_t* Q;
+  const uint16_t* K;
+  int32_t* q_perm;
+  int32_t* kv_perm;
+  float* s_q;
+  float* s_k;
+  float* q_mean;
+  float* k_guide;
+  int Z, H, Hkv, L, S, N;
+  int64_t qs[3], ks[3];
+  void* scratch;
+  size_t scratch_bytes;
+};
+
+size_t plan_scratch_bytes(int Z, int H, int Hkv, int L, int S);
+hipError_t launch_plan(const PlanArgs& a, hipStream_t stream);
+hipError_t launch_attention(const AttnArgs& a, hipStream_t stream);
+
+}  // namespace s2o

@@ -129,17 +129,41 @@ def make_qkv(w: Workload) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     return Q, K, V
 
 
-def redraw_k_rows(w: Workload, K: np.ndarray, z: int, g: int, rows, attempt: int) -> None:
-    """Replace the N(0,1) part of the listed key rows of KV head g by a fresh draw (in
-    place).  Used by test fixtures that want a key set with no two ranking scores
-    closer than a guard gap; what counts as "too close" is decided by the caller."""
-    rows = np.asarray(sorted(int(r) for r in rows), dtype=np.int64)
+def redraw_rows(w: Workload, X: np.ndarray, tensor: str, z: int, head: int, rows, attempt: int,
+                pooled: int = 0) -> None:
+    """Replace the N(0,1) part of the listed rows of Q ("q") or K ("k") head `head` by a
+    fresh draw, in place.  Used by test fixtures that want inputs with no two ranking scores
+    closer than a guard gap; what counts as "too close" is decided by the caller.
+
+    pooled > 0: rows are grouped in consecutive ranges of `pooled` rows whose column sums
+    should stay put (up to bf16 rounding); the change of each range's sum is absorbed by the
+    highest row of the range that is not being re-drawn.  For K only the first range is
+    treated this way."""
+    rows = np.asarray(sorted({int(r) for r in rows}), dtype=np.int64)
     if rows.size == 0:
         return
-    old = bf16_bits_to_f32(K[z, g, rows])
-    base = _rng(w.seed, "k", z, g).standard_normal((w.L, w.D), dtype=np.float32)[rows]
-    fresh = _rng(w.seed, "redraw", z, g, attempt).standard_normal((rows.size, w.D), dtype=np.float32)
-    K[z, g, rows] = f32_to_bf16_bits(old - base + fresh)
+    old = bf16_bits_to_f32(X[z, head, rows])
+    fresh = _rng(w.seed, "redraw", _TENSOR_ID[tensor], z, head, attempt).standard_normal(
+        (rows.size, w.D), dtype=np.float32)
+    # new row = old row with its noise part replaced: the structure (old minus a unit
+    # normal) is not known exactly after earlier re-draws, so mix instead of subtracting
+    new = old + np.float32(0.5) * fresh
+    newbits = f32_to_bf16_bits(new)
+    X[z, head, rows] = newbits
+    if pooled > 0:
+        delta = bf16_bits_to_f32(newbits) - old
+        for rng_id in np.unique(rows // pooled):
+            if tensor == "k" and rng_id != 0:
+                continue
+            sel = rows // pooled == rng_id
+            sink = (rng_id + 1) * pooled - 1
+            taken = set(rows[sel].tolist())
+            while sink in taken:
+                sink -= 1
+            if sink < rng_id * pooled:
+                continue
+            srow = bf16_bits_to_f32(X[z, head, sink]) - delta[sel].sum(axis=0)
+            X[z, head, sink] = f32_to_bf16_bits(srow)
 
 
 # ---------------------------------------------------------------------------

@@ -1,0 +1,188 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs (protocol in tests/parity.py)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import s2o_oracle as orc
+from paper_2602_22575_amd import inputs
+import parity
+import gpu_util as gu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(scope="module")
+def tiny(gpu):
+    import torch
+    w = inputs.workload("tiny")
+    Qb, Kb, Vb = inputs.make_qkv(w)
+    rounds = parity.untie(w, Qb, Kb)
+    _say(f"[tiny] near-tie removal took {rounds} rounds")
+    dev = [gu.to_dev(x) for x in (Qb, Kb, Vb)]
+    return w, (Qb, Kb, Vb), dev
+
+
+def test_tiny_plan_is_exact(tiny):
+    w, (Qb, Kb, Vb), (Qd, Kd, Vd) = tiny
+    _say("case: tiny plan, L=2048 S=256")
+    _, pg = gu.gpu_plan(w, Qd, Kd)
+    stats = parity.check_plan(w, Qb, Kb, pg, exact=True)
+    _say("tiny plan stats", stats)
+    ref = orc.plan(parity.to_f64(Qb), parity.to_f64(Kb), w.S)
+    assert np.array_equal(pg["q_perm"], ref["q_perm"])
+    assert np.array_equal(pg["kv_perm"], ref["kv_perm"])
+
+
+@pytest.mark.parametrize("stop_mode", [0, 1])
+def test_tiny_attention(tiny, stop_mode):
+    w, (Qb, Kb, Vb), (Qd, Kd, Vd) = tiny
+    plan, pg = gu.gpu_plan(w, Qd, Kd)
+    Q, K, V = (parity.to_f64(x) for x in (Qb, Kb, Vb))
+    dense = orc.dense_attention(Q, K, V)
+    gains = orc.gain_profile(Q, K, V, pg["q_perm"], pg["kv_perm"], w.S, w.BM, w.BN, stop_mode=stop_mode)
+    for tau in (0.0, -1.0, 0.02, 0.05, 0.2):
+        if tau > 0:
+            tau = parity.pick_tau(gains, tau)       # fixed by the oracle: no knife-edge decision
+        _say(f"case: tiny attention tau={tau} stop_mode={stop_mode}")
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, stop_mode)
+        st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, stop_mode, Ob, c, s,
+                                    gains=gains)
+        gains = st.pop("gains")
+        _say("  ", st, "density", orc.density(s, w.L, w.S, w.BM, w.BN))
+        if tau <= 0:
+            assert np.all(s == 0) and np.array_equal(c[0, 0], orc.prefix_tiles(w.L, w.S, w.BM, w.BN))
+            err = np.abs(parity.to_f64(Ob) - dense)
+            assert err.max() <= parity.O_MAX_ABS
+            assert (err ** 2).sum() / (dense ** 2).sum() <= parity.O_REL_MSE
+        else:
+            assert st["ambiguous"] == 0          # tau values chosen away from every gain
+            assert (s > 0).any()
+
+
+def test_tiny_arbitrary_maps_reproduce_dense(tiny):
+    """tau = 0 with identity and with random maps: visit order must not matter."""
+    import torch
+    w, (Qb, Kb, Vb), (Qd, Kd, Vd) = tiny
+    Q, K, V = (parity.to_f64(x) for x in (Qb, Kb, Vb))
+    dense = orc.dense_attention(Q, K, V)
+    rng = np.random.default_rng(5)
+    qi, ki = orc.identity_maps(w.Z, w.H, w.L, w.S)
+    qr, kr = qi.copy(), ki.copy()
+    for n in range(w.N):
+        qr[0, 0, n] = rng.permutation(w.S)
+        o = orc.kv_row_offset(n, w.S)
+        kr[0, 0, o:o + n * w.S] = rng.permutation(n * w.S)
+    outs = []
+    for name, (qp, kp), use in (("identity", (qi, ki), 1), ("random", (qr, kr), 1), ("no-qperm", (qr, kr), 0)):
+        _say(f"case: tiny tau=0 maps={name}")
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, torch.from_numpy(qp).cuda(), torch.from_numpy(kp).cuda(),
+                                    0.0, use_q_perm=use)
+        err = np.abs(parity.to_f64(Ob) - dense)
+        assert err.max() <= parity.O_MAX_ABS and (err ** 2).sum() / (dense ** 2).sum() <= parity.O_REL_MSE
+        assert np.all(s == 0)
+        outs.append(parity.to_f64(Ob))
+    assert np.abs(outs[0] - outs[1]).max() <= parity.O_MAX_ABS
+
+
+def test_tiny_without_query_permutation(tiny):
+    """use_q_perm = 0 (the single-pass variant's query order) with the ranked KV map."""
+    w, (Qb, Kb, Vb), (Qd, Kd, Vd) = tiny
+    plan, pg = gu.gpu_plan(w, Qd, Kd)
+    for tau in (0.0, 0.05):
+        _say(f"case: tiny use_q_perm=0 tau={tau}")
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, None, plan.kv_perm, tau, use_q_perm=0)
+        st = parity.check_attention(w, Qb, Kb, Vb, None, pg["kv_perm"], tau, 0, Ob, c, s, use_q_perm=False)
+        st.pop("gains")
+        _say("  ", st)
+    Q, K, V = (parity.to_f64(x) for x in (Qb, Kb, Vb))
+    fused = orc.attention_fused_noqperm(Q, K, V, pg["kv_perm"], w.S, w.BM, w.BN, 0.05)
+    assert np.abs(parity.to_f64(Ob) - fused).max() <= parity.O_MAX_ABS
+
+
+def test_determinism(tiny):
+    w, (Qb, Kb, Vb), (Qd, Kd, Vd) = tiny
+    a_plan, a = gu.gpu_plan(w, Qd, Kd)
+    b_plan, b = gu.gpu_plan(w, Qd, Kd)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    r1 = gu.gpu_attention(w, Qd, Kd, Vd, a_plan.q_perm, a_plan.kv_perm, 0.05)
+    r2 = gu.gpu_attention(w, Qd, Kd, Vd, a_plan.q_perm, a_plan.kv_perm, 0.05)
+    for x, y in zip(r1, r2):
+        assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("L,S,H,Hkv", [(256, 256, 1, 1), (128, 64, 2, 1), (1536, 192, 4, 2), (2048, 1024, 2, 2)])
+def test_edge_shapes(gpu, L, S, H, Hkv):
+    """Single segment (no prefix at all), a one-tile segment (three idle wavefronts), a
+    segment length that is not a power of two, GQA groups."""
+    w = inputs.workload("llama8k", L=L, S=S, H=H, Hkv=Hkv, seed=3)
+    _say(f"case: edge shape L={L} S={S} H={H} Hkv={Hkv}")
+    Qb, Kb, Vb = inputs.make_qkv(w)
+    Qd, Kd, Vd = (gu.to_dev(x) for x in (Qb, Kb, Vb))
+    plan, pg = gu.gpu_plan(w, Qd, Kd)
+    stats = parity.check_plan(w, Qb, Kb, pg)
+    _say("  plan", stats)
+    for tau in (0.0, 0.03):
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau)
+        st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, 0, Ob, c, s)
+        st.pop("gains")
+        _say("  attn", tau, st)
+
+
+def test_degenerate_scores_take_the_fallback_sort(gpu):
+    """All keys equal -> every prefix score of a row is the same number: one bucket holds
+    the whole row and the order must be ascending index (the tie-break)."""
+    import torch
+    w = inputs.workload("llama8k", L=16384, S=1024, H=2, Hkv=1, seed=1)
+    _say("case: degenerate scores, L=16384 S=1024")
+    Qb, Kb, Vb = inputs.make_qkv(w)
+    Kb[:] = Kb[0, 0, 7]
+    Qd, Kd = gu.to_dev(Qb), gu.to_dev(Kb)
+    plan, pg = gu.gpu_plan(w, Qd, Kd)
+    for h in range(2):
+        for n in range(1, w.N):
+            o = orc.kv_row_offset(n, w.S)
+            sk = pg["s_k"][0, h, o:o + n * w.S]
+            assert np.all(sk == sk[0])
+            assert np.array_equal(pg["kv_perm"][0, h, o:o + n * w.S], np.arange(n * w.S))
+    # a few distinct values with massive ties: signs of one coordinate
+    Kb2 = Kb.copy()
+    Kb2[0, 0, ::3, 0] ^= 0x8000
+    plan, pg = gu.gpu_plan(w, Qd, gu.to_dev(Kb2))
+    for n in (1, 9, 15):
+        o = orc.kv_row_offset(n, w.S)
+        sk = pg["s_k"][0, 1, o:o + n * w.S]
+        assert np.array_equal(pg["kv_perm"][0, 1, o:o + n * w.S], np.argsort(-sk, kind="stable"))
+
+
+def test_llama8k(gpu):
+    """Llama-3.1-8B head shape at 8K: full plan parity on every head; attention parity on
+    one query head per KV group over the threshold sweep; tau = 0 against dense."""
+    w = inputs.workload("llama8k")
+    _say("case: llama8k generate")
+    Qb, Kb, Vb = inputs.make_qkv(w)
+    Qd, Kd, Vd = (gu.to_dev(x) for x in (Qb, Kb, Vb))
+    _say("case: llama8k plan")
+    plan, pg = gu.gpu_plan(w, Qd, Kd)
+    stats = parity.check_plan(w, Qb, Kb, pg)
+    _say("  plan stats", stats)
+    heads = [0, 5, 10, 15, 16, 21, 26, 31]
+    gains = None
+    Q, K, V = (parity.to_f64(x) for x in (Qb, Kb, Vb))
+    for tau in w.taus:
+        _say(f"case: llama8k attention tau={tau}")
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau)
+        st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, 0, Ob, c, s,
+                                    heads=heads, gains=gains)
+        gains = st.pop("gains")
+        _say("  ", st, "mean density", float(orc.density(s, w.L, w.S, w.BM, w.BN).mean()))
+        if tau == 0.0:
+            rows = np.arange(0, w.L, 37)
+            for h in heads[:3]:
+                d = orc.dense_attention(Q[:, h:h + 1], K[:, h // w.G:h // w.G + 1], V[:, h // w.G:h // w.G + 1], rows=rows)
+                err = np.abs(parity.to_f64(Ob[0, h, rows]) - d[0, 0])
+                assert err.max() <= parity.O_MAX_ABS
