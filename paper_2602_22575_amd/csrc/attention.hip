@@ -1,14 +1,17 @@
 // S2O sparse attention for gfx950 (paper Sec. 3.2-3.3; Alg. 2 + Alg. 3, Alg. 4 when the
 // query order is the identity).
 //
-// One workgroup = 4 wavefronts = 4 permuted query tiles (4 x 64 rows) of one
-// (batch, head, segment).  All query tiles of a segment walk the same KV_perm row, so the
-// workgroup stages each gathered 64-token K/V tile in LDS once and the four wavefronts share
-// it; every wavefront owns one query tile, keeps its Q fragments, online-softmax state and
-// output accumulator in registers, and takes the early-stop branch on its own (the stop
-// decision is uniform per wavefront).  The dense intra-segment causal window (Pass-1) is
-// run by the same loop before the prefix walk, with identity indices and a per-element
-// causal mask, so its state never leaves registers.
+// One workgroup = 8 wavefronts = 4 permuted query tiles (4 x 64 rows) of one
+// (batch, head, segment); a query tile is owned by a pair of wavefronts, 32 rows each.
+// All query tiles of a segment walk the same KV_perm row, so the workgroup stages each
+// gathered 64-token K/V tile in LDS once and the eight wavefronts share it.  A wavefront
+// keeps its Q fragments, online-softmax state and output accumulator in registers (under
+// 256, so two wavefronts fit on a SIMD and one's softmax overlaps the other's MFMAs).  The
+// early-stop decision of a query tile is the OR of its two wavefronts' "keep" votes,
+// exchanged through LDS at a workgroup barrier; the branch is uniform per wavefront.  The
+// dense intra-segment causal window (Pass-1) is run by the same loop before the prefix
+// walk, with identity indices and a per-element causal mask, so its state never leaves
+// registers.
 //
 // MFMA formulation (v_mfma_f32_32x32x16_bf16), transposed so that a query row lives in
 // one lane pair and softmax statistics need a single cross-lane step:
@@ -21,6 +24,8 @@
 // 16*kk + 8*(jj/4) + 4*hh + jj%4 of the 32-key block; V^T is stored in LDS with the keys of
 // each 16-group permuted accordingly (position 8*hh + 4*a + j holds key 8*a + 4*hh + j), which
 // makes both LDS operand reads plain 16-byte loads.
+#include <type_traits>
+
 #include "s2o_internal.h"
 
 namespace s2o {
@@ -32,13 +37,15 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kD = 128;          // head dim
 constexpr int kBN = 64;          // key tile
-constexpr int kBM = 64;          // query tile (one wavefront)
-constexpr int kWaves = 4;
+constexpr int kBM = 64;          // query tile (two wavefronts)
+constexpr int kTilesPerWg = 4;   // query tiles per workgroup
+constexpr int kWaves = 2 * kTilesPerWg;
+constexpr int kThreads = 64 * kWaves;
 constexpr int kKsStride = 136;   // bf16 elements per K row in LDS (272 B: conflict-free 16 B reads)
 constexpr int kVtStride = 72;    // bf16 elements per V^T row in LDS (144 B)
 constexpr int kKsElems = kBN * kKsStride;
 constexpr int kVtElems = kD * kVtStride;
-constexpr size_t kAttnLds = (size_t)(2 * kKsElems + 2 * kVtElems) * 2 + 64;
+constexpr size_t kAttnLds = (size_t)(2 * kKsElems + 2 * kVtElems) * 2 + 256;
 
 __device__ inline int wave_max_i32(int v) {
 #pragma unroll
@@ -52,17 +59,17 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, t);
 }
 
-__global__ __launch_bounds__(256, 1) void s2o_attention_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
   uint16_t* Vt = Ks + 2 * kKsElems;
-  int* sflag = reinterpret_cast<int*>(Vt + 2 * kVtElems);
+  int* sflag = reinterpret_cast<int*>(Vt + 2 * kVtElems);   // [0..7] pmax, [8..23] active x2, [24..31] keep
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m_ = lane & 31, hh = lane >> 5;
   const int G = a.H / a.Hkv;
-  const int TJ = a.S / kBM;                    // query tiles per segment
-  const int JG = (TJ + kWaves - 1) / kWaves;   // workgroups per (z,h,n)
+  const int TJ = a.S / kBM;                              // query tiles per segment
+  const int JG = (TJ + kTilesPerWg - 1) / kTilesPerWg;   // workgroups per (z,h,n)
 
   // ---- block -> (z, h, n, jg).  Longest prefixes first; when the number of (z, KV head)
   // pairs is a multiple of 8, consecutive block ids (which the dispatcher deals round-robin
@@ -96,35 +103,43 @@ __global__ __launch_bounds__(256, 1) void s2o_attention_kernel(const AttnArgs a)
   const int nS = n * a.S;
   const int nK = nS / kBN;                     // prefix tiles of this segment
 
-  const int j = jg * kWaves + wave;            // this wavefront's permuted query tile
+  // wavefront -> (query tile of the workgroup, 32-row half); the two halves of a tile are
+  // wavefronts w and w + 4
+  const int half = wave >> 2;
+  const int j = jg * kTilesPerWg + (wave & 3);  // this wavefront's permuted query tile
   bool active = j < TJ;
 
-  // ---- query rows of this lane (two: mb = 0, 1) and their Q fragments
-  int qoff[2];
-  bf16x8 qf[2][8];
-#pragma unroll
-  for (int mb = 0; mb < 2; ++mb) {
-    const int r = min(j, TJ - 1) * kBM + 32 * mb + m_;
-    qoff[mb] = a.use_q_perm ? a.q_perm[(zh * a.N + n) * a.S + r] : r;
-    qoff[mb] = min(max(qoff[mb], 0), a.S - 1);
-    const uint16_t* qrow = Qh + (int64_t)(nS + qoff[mb]) * a.qs[2];
+  // ---- the query row of this lane and its Q fragments
+  int qoff;
+  bf16x8 qf[8];
+  {
+    const int r = min(j, TJ - 1) * kBM + 32 * half + m_;
+    qoff = a.use_q_perm ? a.q_perm[(zh * a.N + n) * a.S + r] : r;
+    qoff = min(max(qoff, 0), a.S - 1);
+    const uint16_t* qrow = Qh + (int64_t)(nS + qoff) * a.qs[2];
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk)
-      qf[mb][kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * hh);
+      qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * hh);
   }
-  const int wave_pmax = active ? wave_max_i32(max(qoff[0], qoff[1])) : -1;
+  const int wave_pmax = active ? wave_max_i32(qoff) : -1;
   if (lane == 0) sflag[wave] = wave_pmax;
   __syncthreads();
-  const int wg_pmax = max(max(sflag[0], sflag[1]), max(sflag[2], sflag[3]));
+  int wg_pmax = -1;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) wg_pmax = max(wg_pmax, sflag[w]);
   const int nloc = wg_pmax / kBN + 1;          // own-segment key tiles this workgroup needs
   const int ntiles = nloc + nK;
-  __syncthreads();
 
-  // ---- loader: thread (c, gq) moves 16-byte chunk c of key slots 4*gq .. 4*gq+3
-  const int c = tid & 15, gq = tid >> 4;
+  // ---- loader: wavefronts 0-3 move K, 4-7 move V; thread (c, gq) moves 16-byte chunk c of
+  // key slots 4*gq .. 4*gq+3
+  const int ltid = tid & 255;
+  const bool loads_v = tid >= 256;
+  const int c = ltid & 15, gq = ltid >> 4;
   // V^T position of slot 4*gq: swap bits 0 and 1 of gq (see the header comment)
   const int vpos = 4 * ((gq & ~3) | ((gq & 1) << 1) | ((gq >> 1) & 1));
-  u32x4 kreg[4], vreg[4];
+  const uint16_t* src = loads_v ? Vh : Kh;
+  const int64_t src_stride = loads_v ? a.vs[2] : a.ks[2];
+  u32x4 lreg[4];
   auto load_tile = [&](int it) {
     int tok[4];
     if (it < nloc) {
@@ -137,39 +152,122 @@ __global__ __launch_bounds__(256, 1) void s2o_attention_kernel(const AttnArgs a)
       for (int s = 0; s < 4; ++s) tok[s] = min(max(tok[s], 0), a.L - 1);
     }
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      kreg[s] = *reinterpret_cast<const u32x4*>(Kh + (int64_t)tok[s] * a.ks[2] + 8 * c);
-      vreg[s] = *reinterpret_cast<const u32x4*>(Vh + (int64_t)tok[s] * a.vs[2] + 8 * c);
-    }
+    for (int s = 0; s < 4; ++s)
+      lreg[s] = *reinterpret_cast<const u32x4*>(src + (int64_t)tok[s] * src_stride + 8 * c);
   };
   auto store_tile = [&](int buf) {
-    uint16_t* ks = Ks + buf * kKsElems;
-    uint16_t* vt = Vt + buf * kVtElems;
+    if (!loads_v) {
+      uint16_t* ks = Ks + buf * kKsElems;
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      *reinterpret_cast<u32x4*>(ks + (4 * gq + s) * kKsStride + 8 * c) = kreg[s];
+      for (int s = 0; s < 4; ++s)
+        *reinterpret_cast<u32x4*>(ks + (4 * gq + s) * kKsStride + 8 * c) = lreg[s];
+    } else {
+      uint16_t* vt = Vt + buf * kVtElems;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {   // dword q of a chunk holds dims 8c+2q (low half), 8c+2q+1
-      u32x2 lo, hi;
-      lo.x = (vreg[0][q] & 0xffffu) | (vreg[1][q] << 16);
-      lo.y = (vreg[2][q] & 0xffffu) | (vreg[3][q] << 16);
-      hi.x = (vreg[0][q] >> 16) | (vreg[1][q] & 0xffff0000u);
-      hi.y = (vreg[2][q] >> 16) | (vreg[3][q] & 0xffff0000u);
-      *reinterpret_cast<u32x2*>(vt + (8 * c + 2 * q) * kVtStride + vpos) = lo;
-      *reinterpret_cast<u32x2*>(vt + (8 * c + 2 * q + 1) * kVtStride + vpos) = hi;
+      for (int q = 0; q < 4; ++q) {   // dword q of a chunk holds dims 8c+2q (low half), 8c+2q+1
+        u32x2 lo, hi;
+        lo.x = (lreg[0][q] & 0xffffu) | (lreg[1][q] << 16);
+        lo.y = (lreg[2][q] & 0xffffu) | (lreg[3][q] << 16);
+        hi.x = (lreg[0][q] >> 16) | (lreg[1][q] & 0xffff0000u);
+        hi.y = (lreg[2][q] >> 16) | (lreg[3][q] & 0xffff0000u);
+        *reinterpret_cast<u32x2*>(vt + (8 * c + 2 * q) * kVtStride + vpos) = lo;
+        *reinterpret_cast<u32x2*>(vt + (8 * c + 2 * q + 1) * kVtStride + vpos) = hi;
+      }
     }
   };
 
-  // ---- online-softmax state (base-2 logits) and output accumulator O^T[d-block][mb]
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
-  f32x16 o[4][2];
+  // ---- online-softmax state and output accumulator O^T[d-block].  Logits are kept in
+  // base-2 units (raw score * softmax_scale * log2 e).  m_ref is the reference maximum the
+  // accumulated terms are expressed in; it follows the true running maximum lazily: terms
+  // are only rescaled when the maximum has grown by more than kLazy (2^8), so that in the
+  // common case a tile costs no pass over the accumulator.  Any reference gives the same
+  // result; tile masses and the stop test are ratios in one common reference.
+  constexpr float kLazy = 8.0f;
+  float m_ref = -INFINITY, l_run = 0.f;
+  f32x16 o[4];
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[db][mb][i] = 0.f;
+    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
   int committed = 0, issued = 0;
+  const float c2 = a.scale_log2e;
+
+  // per-tile values handed from the score half of a tile to its PV half
+  f32x16 s[2];
+  float alpha, mass, prev, m_use;
+  bool grow;
+
+  // S^T = K Q^T, softmax numerators (left in s) and the row statistics
+  auto scores = [&](auto local_tag, int it, int buf) {
+    constexpr bool kLocal = decltype(local_tag)::value;
+    const uint16_t* ks = Ks + buf * kKsElems;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[nb][i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(ks + (32 * nb + m_) * kKsStride + 16 * kk + 8 * hh);
+        s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[kk], s[nb], 0, 0, 0);
+      }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        if (kLocal) {
+          const int kpos = it * kBN + 32 * nb + 8 * (i >> 2) + 4 * hh + (i & 3);
+          if (kpos > qoff) s[nb][i] = -INFINITY;     // CausalMask
+        }
+        mx = fmaxf(mx, s[nb][i]);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32)) * c2;
+    grow = mx > m_ref + kLazy;
+    m_use = grow ? mx : m_ref;
+    float sum = 0.f;
+    const float neg = -m_use;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float pe = __builtin_amdgcn_exp2f(fmaf(s[nb][i], c2, neg));
+        s[nb][i] = pe;
+        sum += pe;
+      }
+    sum += __shfl_xor(sum, 32);
+    mass = sum;
+    alpha = grow ? __builtin_amdgcn_exp2f(m_ref - m_use) : 1.0f;
+    prev = l_run * alpha;
+  };
+  // fold the tile into the state: O^T += V^T P^T
+  auto commit = [&](int buf) {
+    const uint16_t* vt = Vt + buf * kVtElems;
+    if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {   // rare: move the accumulator to the new reference
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    }
+    l_run = prev + mass;
+    m_ref = m_use;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2) {
+        u32x4 w;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          w[q] = pack_bf16x2(s[nb][8 * k2 + 2 * q], s[nb][8 * k2 + 2 * q + 1]);
+        const bf16x8 pb = __builtin_bit_cast(bf16x8, w);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          const bf16x8 va = *reinterpret_cast<const bf16x8*>(vt + (32 * db + m_) * kVtStride + 32 * nb + 16 * k2 + 8 * hh);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, o[db], 0, 0, 0);
+        }
+      }
+  };
 
   load_tile(0);
   store_tile(0);
@@ -178,133 +276,56 @@ __global__ __launch_bounds__(256, 1) void s2o_attention_kernel(const AttnArgs a)
   for (int it = 0; it < ntiles; ++it) {
     const int buf = it & 1;
     if (it + 1 < ntiles) load_tile(it + 1);
-
-    const bool local = it < nloc;
-    if (active && !(local && it * kBN > wave_pmax)) {
-      const uint16_t* ks = Ks + buf * kKsElems;
-      const uint16_t* vt = Vt + buf * kVtElems;
-      // S^T = K Q^T
-      f32x16 s[2][2];
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) s[nb][mb][i] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-          const bf16x8 ka = *reinterpret_cast<const bf16x8*>(ks + (32 * nb + m_) * kKsStride + 16 * kk + 8 * hh);
-#pragma unroll
-          for (int mb = 0; mb < 2; ++mb)
-            s[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[mb][kk], s[nb][mb], 0, 0, 0);
-        }
+    if (it < nloc) {
+      if (active && it * kBN <= wave_pmax) {
+        scores(std::true_type{}, it, buf);
+        commit(buf);
       }
-      // online softmax per query row (= per lane and mb)
-      float m_new[2], alpha[2], mass[2], prev[2];
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-        float mx = -INFINITY;
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            float x = s[nb][mb][i] * a.scale_log2e;
-            if (local) {
-              const int kpos = it * kBN + 32 * nb + 8 * (i >> 2) + 4 * hh + (i & 3);
-              x = kpos > qoff[mb] ? -INFINITY : x;     // CausalMask
-            }
-            s[nb][mb][i] = x;
-            mx = fmaxf(mx, x);
-          }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        m_new[mb] = fmaxf(m_run[mb], mx);
-        float sum = 0.f;
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const float p = __builtin_amdgcn_exp2f(s[nb][mb][i] - m_new[mb]);
-            s[nb][mb][i] = p;
-            sum += p;
-          }
-        sum += __shfl_xor(sum, 32);
-        mass[mb] = sum;
-        alpha[mb] = __builtin_amdgcn_exp2f(m_run[mb] - m_new[mb]);
-        prev[mb] = l_run[mb] * alpha[mb];
-      }
-      bool stop = false;
-      if (!local) {
-        // early-stop rule: continue iff some row's tile mass reaches tau * (mass so far)
-        const bool keep = (mass[0] >= a.tau * prev[0]) || (mass[1] >= a.tau * prev[1]);
-        stop = __builtin_amdgcn_ballot_w64(keep) == 0ull;
+    } else {
+      // early-stop rule: the query tile continues iff some row's tile mass reaches
+      // tau * (mass so far); the two wavefronts of the tile vote through LDS
+      bool keep = false;
+      if (active) {
+        scores(std::false_type{}, it, buf);
+        keep = __builtin_amdgcn_ballot_w64(mass >= a.tau * prev) != 0ull;
         ++issued;
       }
-      if (stop) active = false;
-      if (!(stop && a.stop_mode == 0)) {
-        if (!local) ++committed;
-        bf16x8 pb[2][2][2];
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-          l_run[mb] = prev[mb] + mass[mb];
-          m_run[mb] = m_new[mb];
-#pragma unroll
-          for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[db][mb][i] *= alpha[mb];
-#pragma unroll
-          for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int k2 = 0; k2 < 2; ++k2) {
-              u32x4 w;
-#pragma unroll
-              for (int q = 0; q < 4; ++q)
-                w[q] = pack_bf16x2(s[nb][mb][8 * k2 + 2 * q], s[nb][mb][8 * k2 + 2 * q + 1]);
-              pb[nb][mb][k2] = __builtin_bit_cast(bf16x8, w);
-            }
+      if (lane == 0) sflag[24 + wave] = keep ? 1 : 0;
+      __syncthreads();
+      if (active) {
+        const bool stop = (sflag[24 + (wave & 3)] | sflag[24 + 4 + (wave & 3)]) == 0;
+        if (stop) active = false;
+        if (!(stop && a.stop_mode == 0)) {             // a triggering tile is dropped in mode 0
+          commit(buf);
+          ++committed;
         }
-        // O^T += V^T P^T
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-          for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
-              const bf16x8 va = *reinterpret_cast<const bf16x8*>(vt + (32 * db + m_) * kVtStride + 32 * nb + 16 * k2 + 8 * hh);
-#pragma unroll
-              for (int mb = 0; mb < 2; ++mb)
-                o[db][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[nb][mb][k2], o[db][mb], 0, 0, 0);
-            }
       }
     }
-
     if (it + 1 < ntiles) store_tile(buf ^ 1);
-    if (lane == 0) sflag[wave] = active ? 1 : 0;
+    if (lane == 0) sflag[8 + 8 * buf + wave] = active ? 1 : 0;
     __syncthreads();
-    // once the prefix walk has begun, the workgroup leaves when every wavefront has stopped
-    if (it + 1 >= nloc && (sflag[0] | sflag[1] | sflag[2] | sflag[3]) == 0) break;
-    __syncthreads();
+    // the workgroup leaves once every wavefront has stopped (flags alternate between two
+    // sets so that one barrier orders both the tile buffers and the flags)
+    int any = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) any |= sflag[8 + 8 * buf + w];
+    if (any == 0) break;
   }
 
   if (j < TJ) {
-    // normalise and scatter to the original rows: lane holds, for row (mb, m), dims
-    // 32*db + 8*(i/4) + 4*hh + i%4
+    // normalise and scatter to the original row: lane holds dims 32*db + 8*(i/4) + 4*hh + i%4
+    const float inv = 1.0f / l_run;
+    uint16_t* orow = Oh + (int64_t)(nS + qoff) * a.os[2];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-      const float inv = 1.0f / l_run[mb];
-      uint16_t* orow = Oh + (int64_t)(nS + qoff[mb]) * a.os[2];
+    for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          u32x2 w;
-          w.x = pack_bf16x2(o[db][mb][4 * i4] * inv, o[db][mb][4 * i4 + 1] * inv);
-          w.y = pack_bf16x2(o[db][mb][4 * i4 + 2] * inv, o[db][mb][4 * i4 + 3] * inv);
-          *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * i4 + 4 * hh) = w;
-        }
-    }
-    if (lane == 0) {
+      for (int i4 = 0; i4 < 4; ++i4) {
+        u32x2 w;
+        w.x = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
+        w.y = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
+        *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * i4 + 4 * hh) = w;
+      }
+    if (lane == 0 && half == 0) {
       const int64_t ci = zh * (a.L / kBM) + (int64_t)n * TJ + j;
       if (a.computed) a.computed[ci] = committed;
       if (a.skipped) a.skipped[ci] = nK - issued;
@@ -321,10 +342,10 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
     attr_set = true;
   }
   const int TJ = a.S / kBM;
-  const int JG = (TJ + kWaves - 1) / kWaves;
+  const int JG = (TJ + kTilesPerWg - 1) / kTilesPerWg;
   const int64_t blocks = (int64_t)a.Z * a.H * a.N * JG;
   if (blocks <= 0 || blocks > 0x7fffffff) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(s2o_attention_kernel, dim3((unsigned)blocks), dim3(256), kAttnLds, stream, a);
+  hipLaunchKernelGGL(s2o_attention_kernel, dim3((unsigned)blocks), dim3(kThreads), kAttnLds, stream, a);
   return hipGetLastError();
 }
 
