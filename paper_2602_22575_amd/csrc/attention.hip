@@ -205,13 +205,24 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[nb][i] = 0.f;
+    // K fragments are fetched from LDS two contraction steps ahead of the MFMA that uses them
+    bf16x8 ka[3][2];
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk)
+    for (int pre = 0; pre < 2; ++pre)
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(ks + (32 * nb + m_) * kKsStride + 16 * kk + 8 * hh);
-        s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[kk], s[nb], 0, 0, 0);
+      for (int nb = 0; nb < 2; ++nb)
+        ka[pre][nb] = *reinterpret_cast<const bf16x8*>(ks + (32 * nb + m_) * kKsStride + 16 * pre + 8 * hh);
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      if (kk + 2 < 8) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+          ka[(kk + 2) % 3][nb] = *reinterpret_cast<const bf16x8*>(ks + (32 * nb + m_) * kKsStride + 16 * (kk + 2) + 8 * hh);
       }
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+        s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk % 3][nb], qf[kk], s[nb], 0, 0, 0);
+    }
     float mx = -INFINITY;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
@@ -252,64 +263,98 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     }
     l_run = prev + mass;
     m_ref = m_use;
+    // P^T fragments (bf16) for the four 16-key contraction steps
+    bf16x8 pb[4];
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int st = 0; st < 4; ++st) {
+      const int nb = st >> 1, k2 = st & 1;
+      u32x4 w;
 #pragma unroll
-      for (int k2 = 0; k2 < 2; ++k2) {
-        u32x4 w;
+      for (int q = 0; q < 4; ++q)
+        w[q] = pack_bf16x2(s[nb][8 * k2 + 2 * q], s[nb][8 * k2 + 2 * q + 1]);
+      pb[st] = __builtin_bit_cast(bf16x8, w);
+    }
+    // V^T fragments are fetched one contraction step (4 blocks of 32 dims) ahead
+    bf16x8 va[2][4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          w[q] = pack_bf16x2(s[nb][8 * k2 + 2 * q], s[nb][8 * k2 + 2 * q + 1]);
-        const bf16x8 pb = __builtin_bit_cast(bf16x8, w);
+    for (int db = 0; db < 4; ++db)
+      va[0][db] = *reinterpret_cast<const bf16x8*>(vt + (32 * db + m_) * kVtStride + 8 * hh);
 #pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const bf16x8 va = *reinterpret_cast<const bf16x8*>(vt + (32 * db + m_) * kVtStride + 32 * nb + 16 * k2 + 8 * hh);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, o[db], 0, 0, 0);
-        }
+    for (int st = 0; st < 4; ++st) {
+      if (st + 1 < 4) {
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+          va[(st + 1) & 1][db] = *reinterpret_cast<const bf16x8*>(vt + (32 * db + m_) * kVtStride + 16 * (st + 1) + 8 * hh);
       }
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[st & 1][db], pb[st], o[db], 0, 0, 0);
+    }
   };
 
   load_tile(0);
   store_tile(0);
   __syncthreads();
 
-  for (int it = 0; it < ntiles; ++it) {
+  // Every wavefront runs the same sequence of barriers: one per own-segment tile, two per
+  // prefix tile (the stop vote, then the tile-buffer hand-over).  A wavefront whose query
+  // tile has stopped (or that has no query tile) drops into a drain loop that only keeps
+  // loading tiles for the others, so the hot loops carry no "am I still active" merges.
+  int it = 0;
+  // ---- own-segment tiles (Pass-1): dense, causal mask, no stop rule
+  for (; it < nloc; ++it) {
     const int buf = it & 1;
     if (it + 1 < ntiles) load_tile(it + 1);
-    if (it < nloc) {
-      if (active && it * kBN <= wave_pmax) {
-        scores(std::true_type{}, it, buf);
-        commit(buf);
-      }
-    } else {
-      // early-stop rule: the query tile continues iff some row's tile mass reaches
-      // tau * (mass so far); the two wavefronts of the tile vote through LDS
-      bool keep = false;
-      if (active) {
-        scores(std::false_type{}, it, buf);
-        keep = __builtin_amdgcn_ballot_w64(mass >= a.tau * prev) != 0ull;
-        ++issued;
-      }
-      if (lane == 0) sflag[24 + wave] = keep ? 1 : 0;
-      __syncthreads();
-      if (active) {
-        const bool stop = (sflag[24 + (wave & 3)] | sflag[24 + 4 + (wave & 3)]) == 0;
-        if (stop) active = false;
-        if (!(stop && a.stop_mode == 0)) {             // a triggering tile is dropped in mode 0
-          commit(buf);
-          ++committed;
-        }
-      }
+    if (it * kBN <= wave_pmax) {       // wave_pmax = -1 for a wavefront without a query tile
+      scores(std::true_type{}, it, buf);
+      commit(buf);
     }
     if (it + 1 < ntiles) store_tile(buf ^ 1);
-    if (lane == 0) sflag[8 + 8 * buf + wave] = active ? 1 : 0;
     __syncthreads();
-    // the workgroup leaves once every wavefront has stopped (flags alternate between two
-    // sets so that one barrier orders both the tile buffers and the flags)
-    int any = 0;
+  }
+  // ---- prefix tiles in KV_perm order (Pass-2) with the early-stop rule: the query tile
+  // continues iff some row's tile mass reaches tau * (mass so far); the two wavefronts of
+  // the tile vote through LDS
+  bool wg_done = false;
+  if (active) {
+    for (; it < ntiles; ++it) {
+      const int buf = it & 1;
+      if (it + 1 < ntiles) load_tile(it + 1);
+      scores(std::false_type{}, it, buf);
+      const bool keep = __builtin_amdgcn_ballot_w64(mass >= a.tau * prev) != 0ull;
+      ++issued;
+      if (lane == 0) sflag[24 + wave] = keep ? 1 : 0;
+      __syncthreads();
+      const bool stop = (sflag[24 + (wave & 3)] | sflag[24 + 4 + (wave & 3)]) == 0;
+      if (!(stop && a.stop_mode == 0)) {               // a triggering tile is dropped in mode 0
+        commit(buf);
+        ++committed;
+      }
+      if (it + 1 < ntiles) store_tile(buf ^ 1);
+      if (lane == 0) sflag[8 + 8 * buf + wave] = stop ? 0 : 1;
+      __syncthreads();
+      int any = 0;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) any |= sflag[8 + 8 * buf + w];
-    if (any == 0) break;
+      for (int w = 0; w < kWaves; ++w) any |= sflag[8 + 8 * buf + w];
+      if (any == 0) { wg_done = true; ++it; break; }
+      if (stop) { ++it; break; }
+    }
+  }
+  // ---- drain: keep the tile pipeline fed until every wavefront of the workgroup has stopped
+  if (!wg_done) {
+    for (; it < ntiles; ++it) {
+      const int buf = it & 1;
+      if (it + 1 < ntiles) load_tile(it + 1);
+      if (lane == 0) sflag[24 + wave] = 0;
+      __syncthreads();
+      if (it + 1 < ntiles) store_tile(buf ^ 1);
+      if (lane == 0) sflag[8 + 8 * buf + wave] = 0;
+      __syncthreads();
+      int any = 0;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) any |= sflag[8 + 8 * buf + w];
+      if (any == 0) break;
+    }
   }
 
   if (j < TJ) {
