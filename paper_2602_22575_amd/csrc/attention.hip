@@ -21,9 +21,12 @@
 // Lane l = (m = l % 32, hh = l / 32).  A 32x32 accumulator block holds, in register i of lane
 // l, the element [row 8*(i/4) + 4*hh + i%4][column m].  The B operand of the PV product takes
 // registers 8*kk..8*kk+7 of an S^T block as its 8 contraction slots, so slot (hh, jj) is key
-// 16*kk + 8*(jj/4) + 4*hh + jj%4 of the 32-key block; V^T is stored in LDS with the keys of
-// each 16-group permuted accordingly (position 8*hh + 4*a + j holds key 8*a + 4*hh + j), which
-// makes both LDS operand reads plain 16-byte loads.
+// 16*kk + 8*(jj/4) + 4*hh + jj%4 of the 32-key block.  K and V tiles sit row-major (token
+// rows) in LDS.  The K operand is a plain 16-byte read of a row; the V^T operand is read
+// with the transposing LDS load ds_read_b64_tr_b16: within each group of 16 lanes, lane i
+// receives element (i % 4) of the four 8-byte rows pointed to by lanes i/4, 4 + i/4, 8 + i/4
+// and 12 + i/4, so pointing lane r of a group at (key slot r/4, dims 4*(r%4)..+3) hands every
+// lane the four keys of its contraction slots at its own head dimension.
 #include <type_traits>
 
 #include "s2o_internal.h"
@@ -42,9 +45,9 @@ constexpr int kTilesPerWg = 4;   // query tiles per workgroup
 constexpr int kWaves = 2 * kTilesPerWg;
 constexpr int kThreads = 64 * kWaves;
 constexpr int kKsStride = 136;   // bf16 elements per K row in LDS (272 B: conflict-free 16 B reads)
-constexpr int kVtStride = 72;    // bf16 elements per V^T row in LDS (144 B)
+constexpr int kVtStride = 160;   // bf16 elements per V row in LDS (320 B: conflict-free transposing reads)
 constexpr int kKsElems = kBN * kKsStride;
-constexpr int kVtElems = kD * kVtStride;
+constexpr int kVtElems = kBN * kVtStride;
 constexpr size_t kAttnLds = (size_t)(2 * kKsElems + 2 * kVtElems) * 2 + 256;
 
 __device__ inline int wave_max_i32(int v) {
@@ -135,8 +138,6 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   const int ltid = tid & 255;
   const bool loads_v = tid >= 256;
   const int c = ltid & 15, gq = ltid >> 4;
-  // V^T position of slot 4*gq: swap bits 0 and 1 of gq (see the header comment)
-  const int vpos = 4 * ((gq & ~3) | ((gq & 1) << 1) | ((gq >> 1) & 1));
   const uint16_t* src = loads_v ? Vh : Kh;
   const int64_t src_stride = loads_v ? a.vs[2] : a.ks[2];
   u32x4 lreg[4];
@@ -156,24 +157,26 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
       lreg[s] = *reinterpret_cast<const u32x4*>(src + (int64_t)tok[s] * src_stride + 8 * c);
   };
   auto store_tile = [&](int buf) {
-    if (!loads_v) {
-      uint16_t* ks = Ks + buf * kKsElems;
+    uint16_t* dst = loads_v ? Vt + buf * kVtElems : Ks + buf * kKsElems;
+    const int stride = loads_v ? kVtStride : kKsStride;
 #pragma unroll
-      for (int s = 0; s < 4; ++s)
-        *reinterpret_cast<u32x4*>(ks + (4 * gq + s) * kKsStride + 8 * c) = lreg[s];
-    } else {
-      uint16_t* vt = Vt + buf * kVtElems;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {   // dword q of a chunk holds dims 8c+2q (low half), 8c+2q+1
-        u32x2 lo, hi;
-        lo.x = (lreg[0][q] & 0xffffu) | (lreg[1][q] << 16);
-        lo.y = (lreg[2][q] & 0xffffu) | (lreg[3][q] << 16);
-        hi.x = (lreg[0][q] >> 16) | (lreg[1][q] & 0xffff0000u);
-        hi.y = (lreg[2][q] >> 16) | (lreg[3][q] & 0xffff0000u);
-        *reinterpret_cast<u32x2*>(vt + (8 * c + 2 * q) * kVtStride + vpos) = lo;
-        *reinterpret_cast<u32x2*>(vt + (8 * c + 2 * q + 1) * kVtStride + vpos) = hi;
-      }
-    }
+    for (int s = 0; s < 4; ++s)
+      *reinterpret_cast<u32x4*>(dst + (4 * gq + s) * stride + 8 * c) = lreg[s];
+  };
+  // transposing read of 4 keys x this lane's dimension: lane (group g16 = lane/16, r = lane%16)
+  // points at key slot r/4 (+ 4 for the upper lane half), dims 16*(g16&1) + 4*(r%4)
+  const int vt_lane_off = ((lane & 15) >> 2) * kVtStride + 4 * (lane >> 5) * kVtStride
+                          + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  typedef short i16x4 __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+  auto read_vt = [&](const uint16_t* vt, int key0, int db) -> bf16x8 {
+    // contraction slots (hh, jj): jj < 4 -> keys key0 + 4*hh + jj, jj >= 4 -> keys key0 + 8 + 4*hh + jj - 4
+    const uint16_t* p0 = vt + key0 * kVtStride + 32 * db + vt_lane_off;
+    const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p0));
+    const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p0 + 8 * kVtStride));
+    u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+    u32x4 w = {l2.x, l2.y, h2.x, h2.y};
+    return __builtin_bit_cast(bf16x8, w);
   };
 
   // ---- online-softmax state and output accumulator O^T[d-block].  Logits are kept in
@@ -278,13 +281,13 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     bf16x8 va[2][4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
-      va[0][db] = *reinterpret_cast<const bf16x8*>(vt + (32 * db + m_) * kVtStride + 8 * hh);
+      va[0][db] = read_vt(vt, 0, db);
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
       if (st + 1 < 4) {
 #pragma unroll
         for (int db = 0; db < 4; ++db)
-          va[(st + 1) & 1][db] = *reinterpret_cast<const bf16x8*>(vt + (32 * db + m_) * kVtStride + 16 * (st + 1) + 8 * hh);
+          va[(st + 1) & 1][db] = read_vt(vt, 16 * (st + 1), db);
       }
 #pragma unroll
       for (int db = 0; db < 4; ++db)
