@@ -8,7 +8,8 @@
 // keeps its Q fragments, online-softmax state and output accumulator in registers (under
 // 256, so two wavefronts fit on a SIMD and one's softmax overlaps the other's MFMAs).  The
 // early-stop decision of a query tile is the OR of its two wavefronts' "keep" votes,
-// exchanged through LDS at a workgroup barrier; the branch is uniform per wavefront.  The
+// exchanged through LDS at the one workgroup barrier per key tile; the branch is uniform
+// per wavefront and is taken one tile late (the PV product of a tile waits for its vote).  The
 // dense intra-segment causal window (Pass-1) is run by the same loop before the prefix
 // walk, with identity indices and a per-element causal mask, so its state never leaves
 // registers.
@@ -48,7 +49,7 @@ constexpr int kKsStride = 136;   // bf16 elements per K row in LDS (272 B: confl
 constexpr int kVtStride = 160;   // bf16 elements per V row in LDS (320 B: conflict-free transposing reads)
 constexpr int kKsElems = kBN * kKsStride;
 constexpr int kVtElems = kBN * kVtStride;
-constexpr size_t kAttnLds = (size_t)(2 * kKsElems + 2 * kVtElems) * 2 + 256;
+constexpr size_t kAttnLds = (size_t)(2 * kKsElems + 3 * kVtElems) * 2 + 256;
 
 __device__ inline int wave_max_i32(int v) {
 #pragma unroll
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
   uint16_t* Vt = Ks + 2 * kKsElems;
-  int* sflag = reinterpret_cast<int*>(Vt + 2 * kVtElems);   // [0..7] pmax, [8..23] active x2, [24..31] keep
+  int* sflag = reinterpret_cast<int*>(Vt + 3 * kVtElems);   // [0..7] pmax, [8..23] stop votes (two sets)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m_ = lane & 31, hh = lane >> 5;
@@ -156,8 +157,8 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     for (int s = 0; s < 4; ++s)
       lreg[s] = *reinterpret_cast<const u32x4*>(src + (int64_t)tok[s] * src_stride + 8 * c);
   };
-  auto store_tile = [&](int buf) {
-    uint16_t* dst = loads_v ? Vt + buf * kVtElems : Ks + buf * kKsElems;
+  auto store_tile = [&](int it) {       // K tiles alternate between 2 buffers, V tiles between 3
+    uint16_t* dst = loads_v ? Vt + (it % 3) * kVtElems : Ks + (it & 1) * kKsElems;
     const int stride = loads_v ? kVtStride : kKsStride;
 #pragma unroll
     for (int s = 0; s < 4; ++s)
@@ -195,15 +196,14 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   int committed = 0, issued = 0;
   const float c2 = a.scale_log2e;
 
-  // per-tile values handed from the score half of a tile to its PV half
+  // values a tile's score step hands to its PV step
   f32x16 s[2];
   float alpha, mass, prev, m_use;
   bool grow;
 
-  // S^T = K Q^T, softmax numerators (left in s) and the row statistics
-  auto scores = [&](auto local_tag, int it, int buf) {
-    constexpr bool kLocal = decltype(local_tag)::value;
-    const uint16_t* ks = Ks + buf * kKsElems;
+  // S^T = K Q^T for key tile buffer kbuf
+  auto qk = [&](int kbuf) {
+    const uint16_t* ks = Ks + kbuf * kKsElems;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
@@ -226,6 +226,10 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
       for (int nb = 0; nb < 2; ++nb)
         s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk % 3][nb], qf[kk], s[nb], 0, 0, 0);
     }
+  };
+  // softmax numerators (left in s) and the row statistics of the tile
+  auto softmax = [&](auto local_tag, int it) {
+    constexpr bool kLocal = decltype(local_tag)::value;
     float mx = -INFINITY;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
@@ -255,19 +259,8 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     alpha = grow ? __builtin_amdgcn_exp2f(m_ref - m_use) : 1.0f;
     prev = l_run * alpha;
   };
-  // fold the tile into the state: O^T += V^T P^T
-  auto commit = [&](int buf) {
-    const uint16_t* vt = Vt + buf * kVtElems;
-    if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {   // rare: move the accumulator to the new reference
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-    }
-    l_run = prev + mass;
-    m_ref = m_use;
-    // P^T fragments (bf16) for the four 16-key contraction steps
-    bf16x8 pb[4];
+  // P^T fragments (bf16) for the four 16-key contraction steps
+  auto pack_p = [&](bf16x8 (&pb)[4]) {
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
       const int nb = st >> 1, k2 = st & 1;
@@ -277,6 +270,19 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
         w[q] = pack_bf16x2(s[nb][8 * k2 + 2 * q], s[nb][8 * k2 + 2 * q + 1]);
       pb[st] = __builtin_bit_cast(bf16x8, w);
     }
+  };
+  // rare: move the accumulator to a new reference maximum (O^T *= alpha)
+  auto rescale = [&](float al, bool gr) {
+    if (__builtin_amdgcn_ballot_w64(gr) != 0ull) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] *= al;
+    }
+  };
+  // O^T += V^T P^T with the V tile in buffer vbuf
+  auto pv = [&](int vbuf, const bf16x8 (&pb)[4]) {
+    const uint16_t* vt = Vt + vbuf * kVtElems;
     // V^T fragments are fetched one contraction step (4 blocks of 32 dims) ahead
     bf16x8 va[2][4];
 #pragma unroll
@@ -299,64 +305,115 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   store_tile(0);
   __syncthreads();
 
-  // Every wavefront runs the same sequence of barriers: one per own-segment tile, two per
-  // prefix tile (the stop vote, then the tile-buffer hand-over).  A wavefront whose query
-  // tile has stopped (or that has no query tile) drops into a drain loop that only keeps
-  // loading tiles for the others, so the hot loops carry no "am I still active" merges.
+  // Every wavefront runs the same sequence of barriers, one per key tile.  A wavefront whose
+  // query tile has stopped (or that has no query tile) drops into a drain loop that only
+  // keeps loading tiles for the others, so the hot loops carry no "am I still active" merges.
   int it = 0;
   // ---- own-segment tiles (Pass-1): dense, causal mask, no stop rule
   for (; it < nloc; ++it) {
-    const int buf = it & 1;
     if (it + 1 < ntiles) load_tile(it + 1);
     if (it * kBN <= wave_pmax) {       // wave_pmax = -1 for a wavefront without a query tile
-      scores(std::true_type{}, it, buf);
-      commit(buf);
+      qk(it & 1);
+      softmax(std::true_type{}, it);
+      bf16x8 pb[4];
+      pack_p(pb);
+      rescale(alpha, grow);
+      pv(it % 3, pb);
+      l_run = prev + mass;
+      m_ref = m_use;
     }
-    if (it + 1 < ntiles) store_tile(buf ^ 1);
+    if (it + 1 < ntiles) store_tile(it + 1);
     __syncthreads();
   }
   // ---- prefix tiles in KV_perm order (Pass-2) with the early-stop rule: the query tile
-  // continues iff some row's tile mass reaches tau * (mass so far); the two wavefronts of
-  // the tile vote through LDS
+  // continues iff some row's tile mass reaches tau * (mass so far).  The two wavefronts of a
+  // tile vote through LDS; the vote on tile k is written before the barrier that ends step k
+  // and read at the start of step k+1, so the PV product of tile k runs one step late (next
+  // to the scores of tile k+1) and is simply dropped, or folded in as the last one, when the
+  // vote says stop.  The statistics (l, m) are advanced speculatively and rolled back on a
+  // drop; the accumulator is only ever touched by a tile that is kept.
+  bool pending = false;                 // a scored prefix tile waits for its vote
+  bf16x8 pb_pend[4];
+  float alpha_pend = 1.f, l_save = 0.f, m_save = 0.f;
+  bool grow_pend = false;
+  auto vote_flags = [&](int step) { return sflag + 8 + 8 * (step & 1); };
+  auto publish = [&](int step) {        // after softmax of tile `step`: vote + speculative stats
+    const bool keep = __builtin_amdgcn_ballot_w64(mass >= a.tau * prev) != 0ull;
+    if (lane == 0) vote_flags(step)[wave] = keep ? 1 : 0;
+    l_save = l_run; m_save = m_ref;
+    l_run = prev + mass; m_ref = m_use;
+    alpha_pend = alpha; grow_pend = grow;
+    pack_p(pb_pend);
+    pending = true;
+    ++issued;
+  };
   bool wg_done = false;
-  if (active) {
+  if (active && it < ntiles) {
+    // first prefix tile: scores only
+    if (it + 1 < ntiles) load_tile(it + 1);
+    qk(it & 1);
+    softmax(std::false_type{}, it);
+    publish(it);
+    if (it + 1 < ntiles) store_tile(it + 1);
+    __syncthreads();
+    ++it;
     for (; it < ntiles; ++it) {
-      const int buf = it & 1;
+      const int* vf = vote_flags(it - 1);
+      int any = 0;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) any |= vf[w];
+      const bool stop = (vf[wave & 3] | vf[4 + (wave & 3)]) == 0;
+      if (stop && a.stop_mode == 0) {                  // the triggering tile is dropped
+        l_run = l_save; m_ref = m_save;
+        pending = false;
+        wg_done = any == 0;
+        break;
+      }
+      if (stop) {                                      // mode 1: fold it in, then stop
+        rescale(alpha_pend, grow_pend);
+        pv((it - 1) % 3, pb_pend);
+        ++committed;
+        pending = false;
+        wg_done = any == 0;
+        break;
+      }
       if (it + 1 < ntiles) load_tile(it + 1);
-      scores(std::false_type{}, it, buf);
-      const bool keep = __builtin_amdgcn_ballot_w64(mass >= a.tau * prev) != 0ull;
-      ++issued;
-      if (lane == 0) sflag[24 + wave] = keep ? 1 : 0;
+      rescale(alpha_pend, grow_pend);
+      qk(it & 1);
+      pv((it - 1) % 3, pb_pend);
+      ++committed;
+      softmax(std::false_type{}, it);
+      publish(it);
+      if (it + 1 < ntiles) store_tile(it + 1);
       __syncthreads();
-      const bool stop = (sflag[24 + (wave & 3)] | sflag[24 + 4 + (wave & 3)]) == 0;
-      if (!(stop && a.stop_mode == 0)) {               // a triggering tile is dropped in mode 0
-        commit(buf);
+    }
+    if (pending) {                                     // the last prefix tile: its vote is visible now
+      const int* vf = vote_flags(ntiles - 1);
+      const bool stop = (vf[wave & 3] | vf[4 + (wave & 3)]) == 0;
+      if (stop && a.stop_mode == 0) {
+        l_run = l_save; m_ref = m_save;
+      } else {
+        rescale(alpha_pend, grow_pend);
+        pv((ntiles - 1) % 3, pb_pend);
         ++committed;
       }
-      if (it + 1 < ntiles) store_tile(buf ^ 1);
-      if (lane == 0) sflag[8 + 8 * buf + wave] = stop ? 0 : 1;
-      __syncthreads();
-      int any = 0;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) any |= sflag[8 + 8 * buf + w];
-      if (any == 0) { wg_done = true; ++it; break; }
-      if (stop) { ++it; break; }
+      wg_done = true;
     }
   }
-  // ---- drain: keep the tile pipeline fed until every wavefront of the workgroup has stopped
+  // ---- drain: keep the tile pipeline fed until every query tile of the workgroup has stopped
   if (!wg_done) {
     for (; it < ntiles; ++it) {
-      const int buf = it & 1;
-      if (it + 1 < ntiles) load_tile(it + 1);
-      if (lane == 0) sflag[24 + wave] = 0;
-      __syncthreads();
-      if (it + 1 < ntiles) store_tile(buf ^ 1);
-      if (lane == 0) sflag[8 + 8 * buf + wave] = 0;
-      __syncthreads();
-      int any = 0;
+      if (it > nloc) {
+        const int* vf = vote_flags(it - 1);
+        int any = 0;
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) any |= sflag[8 + 8 * buf + w];
-      if (any == 0) break;
+        for (int w = 0; w < kWaves; ++w) any |= vf[w];
+        if (any == 0) break;
+      }
+      if (it + 1 < ntiles) load_tile(it + 1);
+      if (lane == 0) vote_flags(it)[wave] = 0;
+      if (it + 1 < ntiles) store_tile(it + 1);
+      __syncthreads();
     }
   }
 
