@@ -75,27 +75,31 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   const int TJ = a.S / kBM;                              // query tiles per segment
   const int JG = (TJ + kTilesPerWg - 1) / kTilesPerWg;   // workgroups per (z,h,n)
 
-  // ---- block -> (z, h, n, jg).  Longest prefixes first; when the number of (z, KV head)
-  // pairs is a multiple of 8, consecutive block ids (which the dispatcher deals round-robin
-  // to the 8 XCDs) are mapped so that all work on one KV head stays on one XCD's L2.
+  // ---- block -> (z, h, n, jg).  Longest prefixes first.  Consecutive block ids are dealt
+  // round-robin to the 8 XCDs, each with its own L2: the JG workgroups of one (z, h, n) walk
+  // the same KV_perm row at about the same time, so they are given ids that land on one XCD
+  // (their gathered K/V tiles then hit in that L2), while the XCD of a head rotates with the
+  // segment so that heads that stop early and heads that never stop mix evenly on every XCD.
   int z, h, n, jg;
   {
-    const int U = a.Z * a.Hkv;
-    int b = blockIdx.x, unit, rest;
-    if (U % 8 == 0) {
-      const int xcd = b & 7, idx = b >> 3, per = U / 8;
-      unit = (idx % per) * 8 + xcd;
-      rest = idx / per;
+    const int ZH = a.Z * a.H;
+    const int b = blockIdx.x;
+    int zh_, nr;
+    if (ZH % 8 == 0) {
+      const int xcd = b & 7, idx = b >> 3, per = ZH / 8;
+      jg = idx % JG;
+      const int unit = idx / JG;
+      nr = unit / per;
+      zh_ = ((xcd - nr) & 7) + 8 * (unit % per);
     } else {
-      unit = b % U;
-      rest = b / U;
+      jg = b % JG;
+      const int unit = b / JG;
+      nr = unit / ZH;
+      zh_ = unit % ZH;
     }
-    jg = rest % JG; rest /= JG;
-    const int hq = rest % G; rest /= G;
-    n = a.N - 1 - rest;
-    z = unit / a.Hkv;
-    const int g = unit % a.Hkv;
-    h = g * G + hq;
+    n = a.N - 1 - nr;
+    z = zh_ / a.H;
+    h = zh_ % a.H;
   }
   const int g = h / G;
   const uint16_t* Qh = a.Q + z * a.qs[0] + h * a.qs[1];
