@@ -104,7 +104,7 @@ int s2o_plan(const void* Q, const void* K, const s2o_params* params, const s2o_p
   if (!Q || !K || !out || !out->q_perm) return S2O_EINVAL;
   if (s.N > 1 && !out->kv_perm) return S2O_EINVAL;
   if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(out->q_perm, 16) ||
-      misaligned(out->kv_perm, 16))
+      misaligned(out->kv_perm, 16) || misaligned(out->s_k, 16))
     return S2O_EINVAL;
   const size_t need = s2o::plan_scratch_bytes(s.Z, s.H, s.Hkv, s.L, s.S);
   if (!scratch || misaligned(scratch, 256) || scratch_bytes < need) return S2O_ESCRATCH;

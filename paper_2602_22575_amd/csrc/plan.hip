@@ -5,35 +5,52 @@
 //                        segment's Q rows gives q_mean and s_Q; the S scores are then
 //                        Argsort-ed in LDS (bitonic network on 64-bit keys) -> Q_perm.
 //   score_kernel<MODE>   s_K[n, t] = <q_mean[n], K[t]> as an MFMA contraction per KV head:
-//                        rows = (query head of the group, segment), columns = key tokens.
-//                        q_mean is split exactly into three bf16 terms so that bf16 MFMA
-//                        reproduces the fp32 x bf16 products exactly (fp32 accumulation).
-//                        The kernel is run three times with different epilogues:
-//                        MODE 0 row min/max (+ optional s_K store), MODE 1 bucket
-//                        histogram, MODE 2 scatter of (key, token) pairs into buckets.
-//   scan_kernel          per prefix row: bucket offsets and a list of spans (runs of
-//                        consecutive buckets that fit the LDS sort).
+//                        columns = (query head of the group, segment), rows = key tokens
+//                        staged through LDS.  q_mean is split exactly into three bf16 terms
+//                        so that bf16 MFMA reproduces the fp32 x bf16 products exactly (fp32
+//                        accumulation).  The Argsort of a prefix row (up to L - S scores) is
+//                        a bucket sort on the score value, so the kernel runs three times
+//                        with different epilogues:
+//                          MODE 0  row min / max (+ optional s_K store)
+//                          MODE 1  per (row, 1024-token chunk) bucket counts, kept in LDS
+//                                  and written once per chunk (no global atomics)
+//                          MODE 2  scatter of (key, token) pairs to their bucket: global
+//                                  offset of the (row, chunk, bucket) cell + a rank taken
+//                                  from an LDS counter
+//                        Re-computing the scores costs K reads (0.27 GB at 128K, from the
+//                        last-level cache after the first pass) instead of a round trip of
+//                        the 0.53 GB score array.
+//   scan_kernel          per prefix row: cell offsets (bucket-major, chunk-minor) and the
+//                        list of spans (runs of consecutive buckets that fit the LDS sort).
 //   span_sort_kernel     sorts each span in LDS and writes the token indices at their
-//                        final ranks -> KV_perm.
+//                        final ranks -> KV_perm.  Linear-time: a second, fine bucketing on
+//                        the score value leaves ~2 keys per sub-bucket, which are ranked by
+//                        direct comparison; a span whose keys pile up in one sub-bucket
+//                        (many equal scores) falls back to a bitonic network.
 //   big_sort_kernel      fallback for a bucket that alone exceeds the LDS sort (e.g. all
 //                        scores equal): a stable LSD radix sort by one workgroup.
 //
-// Argsort semantics: descending score, ties by ascending index, -0 == +0.  Both sorts work
+// Argsort semantics: descending score, ties by ascending index, -0 == +0.  Every sort works
 // on the 64-bit key (~ordered(score)) << 32 | index, whose ascending order is exactly
-// that order, so no stability property of the network is needed.
+// that order, so no stability property is needed anywhere.
 #include "s2o_internal.h"
 
 namespace s2o {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kD = 128;
-constexpr int kNBMax = 512;        // buckets per prefix row (upper bound)
-constexpr int kBucketAvg = 256;    // target average bucket population
+constexpr int kNBMax = 128;        // buckets per prefix row (upper bound)
+constexpr int kBucketAvg = 1024;   // target average bucket population
 constexpr int kSpanCap = 4096;     // elements one span_sort workgroup sorts in LDS
-constexpr int kTokChunk = 1024;    // key tokens per score workgroup
+constexpr int kSubBuckets = 2048;  // fine buckets of the in-LDS sort
+constexpr int kSubMax = 64;        // a fuller sub-bucket sends the span to the bitonic fallback
+constexpr int kChunk = 1024;       // key tokens per score workgroup
+constexpr int kSub = 128;          // key tokens per LDS tile of the score kernel
+constexpr int kKStride = 136;      // bf16 elements per K row in LDS (272 B)
 constexpr int kBigGrid = 64;       // workgroups of the fallback sort
 
 __host__ __device__ inline int row_buckets(int n, int S) {
@@ -64,14 +81,15 @@ struct Scratch {
   uint16_t* qsplit;   // [Z*H*N][3][128] bf16
   uint32_t* rowmin;   // [Z*H*N] ordered-u32
   uint32_t* rowmax;   // [Z*H*N]
-  uint32_t* hist;     // [Z*H*N*kNBMax]
-  uint32_t* cursor;   // [Z*H*N*kNBMax]
+  uint16_t* chist;    // [Z*H*N][maxch][kNBMax] bucket counts per 1024-token chunk
+  uint32_t* coffs;    // same shape: offset of the cell inside its row
   uint32_t* counters; // [0]=#spans [1]=#big spans [2]=error flag
   int4* spans;        // [max_spans]  (row, begin, end, 0)
   int4* bigspans;     // [max_spans]
   uint64_t* pairs;    // [Z*H*P]
   uint64_t* alt;      // [kBigGrid * L]
   int64_t max_spans;
+  int maxch;
   size_t total;
 };
 
@@ -83,6 +101,7 @@ static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S) {
   const int64_t P = kv_row_offset(N, S);
   Scratch s;
   s.max_spans = (int64_t)Z * H * (3 * P / kSpanCap + 2 * N) + 8;
+  s.maxch = (L + kChunk - 1) / kChunk;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return (char*)base + o; };
   s.kguide = (float*)take((size_t)Z * Hkv * kD * 4);
@@ -90,8 +109,8 @@ static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S) {
   s.qsplit = (uint16_t*)take((size_t)rows * 3 * kD * 2);
   s.rowmin = (uint32_t*)take((size_t)rows * 4);
   s.rowmax = (uint32_t*)take((size_t)rows * 4);
-  s.hist = (uint32_t*)take((size_t)rows * kNBMax * 4);
-  s.cursor = (uint32_t*)take((size_t)rows * kNBMax * 4);
+  s.chist = (uint16_t*)take((size_t)rows * s.maxch * kNBMax * 2);
+  s.coffs = (uint32_t*)take((size_t)rows * s.maxch * kNBMax * 4);
   s.counters = (uint32_t*)take(64);
   s.spans = (int4*)take((size_t)s.max_spans * 16);
   s.bigspans = (int4*)take((size_t)s.max_spans * 16);
@@ -108,7 +127,6 @@ size_t plan_scratch_bytes(int Z, int H, int Hkv, int L, int S) {
 // ---------------------------------------------------------------------------------------
 __global__ void init_kernel(Scratch s, int64_t rows) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < rows * kNBMax) s.hist[i] = 0;
   if (i < rows) { s.rowmin[i] = 0xffffffffu; s.rowmax[i] = 0u; }
   if (i < 16) s.counters[i] = 0;
 }
@@ -224,180 +242,240 @@ __global__ __launch_bounds__(256) void pool_sq_sort_kernel(PlanArgs a, Scratch s
 }
 
 // ---------------------------------------------------------------------------------------
-// s_K scoring.  Workgroup = (z, g, row block of 32 rows, chunk of kTokChunk tokens); each of
-// the 4 wavefronts takes 32-token column blocks of the chunk.  Row r of KV head g is
-// (hq = r / N, n = r % N) and needs tokens t < n*S.
-//   A (32 rows x 16 dims)  : q_mean split terms, lane (row = l%32, hh = l/32) holds dims
-//                            64*hh + 8*kk .. +8 for contraction step kk
-//   B (16 dims x 32 tokens): lane (token = l%32, hh) holds the same dims of its K row, i.e.
-//                            each lane streams one contiguous 128-byte half row
-//   C (32 rows x 32 tokens): register i of lane l = [row 8*(i/4) + 4*hh + i%4][token l%32]
+// s_K scoring.  Workgroup = (z, g, group of 4 row blocks, chunk of kChunk tokens); wavefront w
+// owns row block 4*group + w (32 rows of the contraction's N side) and keeps its q_mean split
+// fragments in registers for the whole chunk; the chunk's K rows pass through LDS in tiles
+// of kSub tokens shared by the four wavefronts.  Row r of KV head g is (hq = r / N,
+// n = r % N) and needs tokens t < n*S.
+//   A (32 tokens x 16 dims): K tile rows from LDS, lane (token = l%32, hh = l/32) reads dims
+//                            16*kk + 8*hh .. +8
+//   B (16 dims x 32 rows)  : q_mean split terms, lane (row = l%32, hh) holds the same dims
+//   C (32 tokens x 32 rows): register i of lane l = [token 8*(i/4) + 4*hh + i%4][row l%32],
+//                            so a lane sees one row only and its meta data are scalars
 template <int MODE>
 __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t* Kt = reinterpret_cast<uint16_t*>(smem);                          // [kSub][kKStride]
+  uint32_t* hist_all = reinterpret_cast<uint32_t*>(smem + kSub * kKStride * 2);  // [4][32][kNBMax/2]
+
   const int G = a.H / a.Hkv;
   const int R = G * a.N;
-  const int RB = (R + 31) / 32;
-  const int nchunks = (a.L + kTokChunk - 1) / kTokChunk;
-  int b = blockIdx.x;
-  const int chunk = b % nchunks; b /= nchunks;
-  const int rb = b % RB; b /= RB;
-  const int g = b % a.Hkv;
-  const int z = b / a.Hkv;
+  const int nchunks = (a.L + kChunk - 1) / kChunk;
+  // all work on one KV head goes to one XCD (block ids are dealt round-robin to the 8 XCDs):
+  // the scatter pass appends to ~R*kNBMax open cache lines per head, which fit one L2
+  int unit, rest;
+  {
+    const int U = a.Z * a.Hkv, b = blockIdx.x;
+    if (U % 8 == 0) {
+      const int xcd = b & 7, idx = b >> 3, per = U / 8;
+      unit = (idx % per) * 8 + xcd;
+      rest = idx / per;
+    } else {
+      unit = b % U;
+      rest = b / U;
+    }
+  }
+  const int chunk = rest % nchunks;
+  const int rbg = rest / nchunks;
+  const int g = unit % a.Hkv, z = unit / a.Hkv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m_ = lane & 31, hh = lane >> 5;
+  const int rb = 4 * rbg + wave;
 
-  // token limit of the block's rows
-  int limmax = 0;
-  for (int i = 0; i < 32; ++i) {
-    const int r = rb * 32 + i;
-    if (r < R) limmax = max(limmax, (r % a.N) * a.S);
-  }
-  const int t_begin = chunk * kTokChunk;
-  if (t_begin >= limmax) return;
-  const int t_end = min(t_begin + kTokChunk, limmax);
+  auto row_limit = [&](int r) { return r < R ? (r % a.N) * a.S : 0; };
+  // token limits: of the workgroup's rows (uniform) and of this wavefront's rows
+  int lim_wg = 0, lim_wave = 0;
+  for (int i = 0; i < 128; ++i) lim_wg = max(lim_wg, row_limit(128 * rbg + i));
+  for (int i = 0; i < 32; ++i) lim_wave = max(lim_wave, row_limit(32 * rb + i));
+  const int t_begin = chunk * kChunk;
+  if (t_begin >= lim_wg) return;
+  const int t_end = min(t_begin + kChunk, lim_wg);
 
-  // per-register row data: rows of this lane's 16 accumulator registers
-  int64_t row_id[16];      // (z*H + h)*N + n, or -1
-  int lim[16];
-  int64_t base[16];        // packed offset of the row inside s_k / pairs
-  const int64_t P = kv_row_offset(a.N, a.S);
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int r = rb * 32 + 8 * (i >> 2) + 4 * hh + (i & 3);
-    if (r < R) {
-      const int hq = r / a.N, n = r % a.N;
-      const int64_t zh = (int64_t)z * a.H + g * G + hq;
-      row_id[i] = zh * a.N + n;
-      lim[i] = n * a.S;
-      base[i] = zh * P + kv_row_offset(n, a.S);
-    } else {
-      row_id[i] = -1; lim[i] = 0; base[i] = 0;
-    }
+  // this lane's row
+  const int r = 32 * rb + m_;
+  const int lim = row_limit(r);
+  const int rr = min(r, R - 1);
+  const int64_t zh = (int64_t)z * a.H + g * G + rr / a.N;
+  const int64_t row_id = zh * a.N + rr % a.N;
+  const int64_t base = zh * kv_row_offset(a.N, a.S) + kv_row_offset(rr % a.N, a.S);
+  float rhi = 0.f, rscale = 0.f;
+  int rnb = 1;
+  if (MODE != 0 && lim > 0) {
+    const float lo = ordered_to_float(sc.rowmin[row_id]);
+    rhi = ordered_to_float(sc.rowmax[row_id]);
+    rnb = row_buckets(lim / a.S, a.S);
+    const float range = rhi - lo;
+    rscale = range > 0.f ? (float)rnb / range : 0.f;
   }
-  float rhi[16], rscale[16];
-  int rnb[16];
-  if (MODE != 0) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      rhi[i] = 0.f; rscale[i] = 0.f; rnb[i] = 1;
-      if (lim[i] > 0) {
-        const float lo = ordered_to_float(sc.rowmin[row_id[i]]);
-        rhi[i] = ordered_to_float(sc.rowmax[row_id[i]]);
-        rnb[i] = row_buckets(lim[i] / a.S, a.S);
-        const float range = rhi[i] - lo;
-        rscale[i] = range > 0.f ? (float)rnb[i] / range : 0.f;
-      }
-    }
-  }
+  const int64_t cell = (row_id * sc.maxch + chunk) * kNBMax;
 
-  // A fragments: 3 split terms x 8 contraction steps
-  bf16x8 af[3][8];
+  // B fragments: 3 split terms x 8 contraction steps
+  bf16x8 bq[3][8];
   {
-    const int r = min(rb * 32 + m_, R - 1);
-    const int hq = r / a.N, n = r % a.N;
-    const int64_t rid = ((int64_t)z * a.H + g * G + hq) * a.N + n;
-    const uint16_t* qs = sc.qsplit + rid * 3 * kD;
+    const uint16_t* qs = sc.qsplit + row_id * 3 * kD;
 #pragma unroll
     for (int t = 0; t < 3; ++t)
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk)
-        af[t][kk] = *reinterpret_cast<const bf16x8*>(qs + t * kD + 64 * hh + 8 * kk);
+        bq[t][kk] = *reinterpret_cast<const bf16x8*>(qs + t * kD + 16 * kk + 8 * hh);
   }
 
+  uint32_t* hist = hist_all + wave * 32 * (kNBMax / 2);   // two 16-bit counters per word
+  if (MODE != 0) {
+    for (int i = lane; i < 32 * (kNBMax / 2); i += 64) hist[i] = 0;
+  }
+
+  // K tile loader: thread (c, q) moves 16-byte chunk c of rows q, q+16, ...
   const uint16_t* Kh = a.K + z * a.ks[0] + g * a.ks[1];
-  float vmin[16], vmax[16];
+  const int c = tid & 15, q = tid >> 4;
+  u32x4 kreg[8];
+  auto load_tile = [&](int t0) {
 #pragma unroll
-  for (int i = 0; i < 16; ++i) { vmin[i] = INFINITY; vmax[i] = -INFINITY; }
+    for (int s = 0; s < 8; ++s) {
+      const int t = min(t0 + q + 16 * s, a.L - 1);
+      kreg[s] = *reinterpret_cast<const u32x4*>(Kh + (int64_t)t * a.ks[2] + 8 * c);
+    }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+      *reinterpret_cast<u32x4*>(Kt + (q + 16 * s) * kKStride + 8 * c) = kreg[s];
+  };
 
-  for (int t0 = t_begin + wave * 32; t0 < t_end; t0 += 4 * 32) {
-    const int t = t0 + m_;                       // this lane's token (column)
-    const uint16_t* krow = Kh + (int64_t)min(t, a.L - 1) * a.ks[2] + 64 * hh;
-    bf16x8 kf[8];
+  float vmin = INFINITY, vmax = -INFINITY;
+  load_tile(t_begin);
+  for (int t0 = t_begin; t0 < t_end; t0 += kSub) {
+    __syncthreads();                       // previous tile fully consumed
+    store_tile();
+    __syncthreads();
+    if (t0 + kSub < t_end) load_tile(t0 + kSub);
+    if (t0 < lim_wave) {
+#pragma unroll 1
+      for (int sb = 0; sb < 4; ++sb) {
+        f32x16 acc;
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) kf[kk] = *reinterpret_cast<const bf16x8*>(krow + 8 * kk);
-    f32x16 acc;
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+        bf16x8 ka[8];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-    // smallest term first so that the large products meet an accumulator that already
-    // holds the corrections
+        for (int kk = 0; kk < 8; ++kk)
+          ka[kk] = *reinterpret_cast<const bf16x8*>(Kt + (32 * sb + m_) * kKStride + 16 * kk + 8 * hh);
+        // smallest term first so that the large products meet an accumulator that already
+        // holds the corrections
 #pragma unroll
-    for (int tt = 2; tt >= 0; --tt)
+        for (int tt = 2; tt >= 0; --tt)
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk)
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[tt][kk], kf[kk], acc, 0, 0, 0);
-
+          for (int kk = 0; kk < 8; ++kk)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], bq[tt][kk], acc, 0, 0, 0);
+        // the four registers of a group are four consecutive tokens
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      if (t < lim[i]) {
-        const float s = acc[i];
-        if (MODE == 0) {
-          vmin[i] = fminf(vmin[i], s);
-          vmax[i] = fmaxf(vmax[i], s);
-          if (a.s_k) a.s_k[base[i] + t] = s;
-        } else {
-          int bk = (int)((rhi[i] - s) * rscale[i]);
-          bk = min(max(bk, 0), rnb[i] - 1);
-          if (MODE == 1) {
-            atomicAdd(&sc.hist[row_id[i] * kNBMax + bk], 1u);
-          } else {
-            const uint32_t pos = atomicAdd(&sc.cursor[row_id[i] * kNBMax + bk], 1u);
-            if (pos < (uint32_t)lim[i]) sc.pairs[base[i] + pos] = sort_key(s, (uint32_t)t);
-            else sc.counters[2] = 1u;
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const int t = t0 + 32 * sb + 8 * i4 + 4 * hh;
+          if (t < lim) {                   // lim is a multiple of 64: all four or none
+            if (MODE == 0) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                vmin = fminf(vmin, acc[4 * i4 + e]);
+                vmax = fmaxf(vmax, acc[4 * i4 + e]);
+              }
+              if (a.s_k) {
+                const f32x4 v = {acc[4 * i4], acc[4 * i4 + 1], acc[4 * i4 + 2], acc[4 * i4 + 3]};
+                *reinterpret_cast<f32x4*>(a.s_k + base + t) = v;
+              }
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const float sv = acc[4 * i4 + e];
+                int bk = (int)((rhi - sv) * rscale);
+                bk = min(max(bk, 0), rnb - 1);
+                const uint32_t inc = 1u << (16 * (bk & 1));
+                if (MODE == 1) {
+                  atomicAdd(&hist[m_ * (kNBMax / 2) + (bk >> 1)], inc);
+                } else {
+                  const uint32_t w = atomicAdd(&hist[m_ * (kNBMax / 2) + (bk >> 1)], inc);
+                  const uint32_t rank = (w >> (16 * (bk & 1))) & 0xffffu;
+                  const uint32_t pos = sc.coffs[cell + bk] + rank;
+                  if (pos < (uint32_t)lim) sc.pairs[base + pos] = sort_key(sv, (uint32_t)(t + e));
+                  else sc.counters[2] = 1u;
+                }
+              }
+            }
           }
         }
       }
     }
   }
   if (MODE == 0) {
-    // reduce over the 32 token lanes of each half, then one atomic per row
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      float lo = vmin[i], hi = vmax[i];
-#pragma unroll
-      for (int o = 16; o > 0; o >>= 1) {
-        lo = fminf(lo, __shfl_xor(lo, o));
-        hi = fmaxf(hi, __shfl_xor(hi, o));
-      }
-      if (m_ == 0 && lim[i] > 0 && lo <= hi) {
-        atomicMin(&sc.rowmin[row_id[i]], ordered_u32(lo));
-        atomicMax(&sc.rowmax[row_id[i]], ordered_u32(hi));
+    if (lim > 0 && vmin <= vmax) {
+      atomicMin(&sc.rowmin[row_id], ordered_u32(vmin));
+      atomicMax(&sc.rowmax[row_id], ordered_u32(vmax));
+    }
+  }
+  if (MODE == 1) {
+    // counts of this (row block, chunk): one 256-byte row of kNBMax 16-bit counters per row
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_wave_barrier();
+    for (int i = 0; i < 32; ++i) {
+      const int r2 = 32 * rb + i;
+      if (row_limit(r2) > t_begin) {
+        const int64_t zh2 = (int64_t)z * a.H + g * G + r2 / a.N;
+        const int64_t cell2 = ((zh2 * a.N + r2 % a.N) * sc.maxch + chunk) * kNBMax;
+        reinterpret_cast<uint32_t*>(sc.chist + cell2)[lane] = hist[i * (kNBMax / 2) + lane];
       }
     }
   }
 }
 
-// Per prefix row: exclusive scan of the bucket histogram -> scatter cursors, and the list
+// Per prefix row: offsets of the (chunk, bucket) cells in bucket-major order, and the list
 // of spans handed to the sort kernels.
-__global__ __launch_bounds__(64) void scan_kernel(PlanArgs a, Scratch sc) {
+__global__ __launch_bounds__(kNBMax) void scan_kernel(PlanArgs a, Scratch sc) {
+  __shared__ uint32_t tot[kNBMax];
+  __shared__ uint32_t bstart[kNBMax + 1];
   const int64_t row_id = blockIdx.x;
   const int n = (int)(row_id % a.N);
   if (n == 0) return;
-  if (threadIdx.x != 0) return;
+  const int b = threadIdx.x;
   const int nb = row_buckets(n, a.S);
-  uint32_t* hist = sc.hist + row_id * kNBMax;
-  uint32_t* cur = sc.cursor + row_id * kNBMax;
-  uint32_t off = 0, span_begin = 0;
-  for (int b = 0; b < nb; ++b) {
-    const uint32_t cnt = hist[b];
-    cur[b] = off;
-    if (cnt > (uint32_t)kSpanCap) {
-      if (off > span_begin) {
+  const int nch = (n * a.S + kChunk - 1) / kChunk;
+  const uint16_t* ch = sc.chist + row_id * sc.maxch * kNBMax;
+  uint32_t* co = sc.coffs + row_id * sc.maxch * kNBMax;
+  uint32_t t = 0;
+  if (b < nb)
+    for (int c = 0; c < nch; ++c) t += ch[c * kNBMax + b];
+  tot[b] = t;
+  __syncthreads();
+  if (b == 0) {
+    uint32_t off = 0, span_begin = 0;
+    for (int k = 0; k < nb; ++k) {
+      const uint32_t cnt = tot[k];
+      bstart[k] = off;
+      if (cnt > (uint32_t)kSpanCap) {
+        if (off > span_begin) {
+          const uint32_t s = atomicAdd(&sc.counters[0], 1u);
+          if ((int64_t)s < sc.max_spans) sc.spans[s] = make_int4((int)row_id, (int)span_begin, (int)off, 0);
+        }
+        const uint32_t s = atomicAdd(&sc.counters[1], 1u);
+        if ((int64_t)s < sc.max_spans) sc.bigspans[s] = make_int4((int)row_id, (int)off, (int)(off + cnt), 0);
+        span_begin = off + cnt;
+      } else if (off + cnt - span_begin > (uint32_t)kSpanCap) {
         const uint32_t s = atomicAdd(&sc.counters[0], 1u);
         if ((int64_t)s < sc.max_spans) sc.spans[s] = make_int4((int)row_id, (int)span_begin, (int)off, 0);
+        span_begin = off;
       }
-      const uint32_t s = atomicAdd(&sc.counters[1], 1u);
-      if ((int64_t)s < sc.max_spans) sc.bigspans[s] = make_int4((int)row_id, (int)off, (int)(off + cnt), 0);
-      span_begin = off + cnt;
-    } else if (off + cnt - span_begin > (uint32_t)kSpanCap) {
+      off += cnt;
+    }
+    if (off > span_begin) {
       const uint32_t s = atomicAdd(&sc.counters[0], 1u);
       if ((int64_t)s < sc.max_spans) sc.spans[s] = make_int4((int)row_id, (int)span_begin, (int)off, 0);
-      span_begin = off;
     }
-    off += cnt;
+    if (off != (uint32_t)(n * a.S)) sc.counters[2] = 2u;
   }
-  if (off > span_begin) {
-    const uint32_t s = atomicAdd(&sc.counters[0], 1u);
-    if ((int64_t)s < sc.max_spans) sc.spans[s] = make_int4((int)row_id, (int)span_begin, (int)off, 0);
+  __syncthreads();
+  if (b < nb) {
+    uint32_t running = bstart[b];
+    for (int c = 0; c < nch; ++c) {
+      co[c * kNBMax + b] = running;
+      running += ch[c * kNBMax + b];
+    }
   }
 }
 
@@ -409,15 +487,89 @@ __device__ inline int64_t row_base(const PlanArgs& a, int64_t row_id) {
 
 __global__ __launch_bounds__(256) void span_sort_kernel(PlanArgs a, Scratch sc) {
   __shared__ uint64_t keys[kSpanCap];
-  if (blockIdx.x >= sc.counters[0]) return;
-  const int4 sp = sc.spans[blockIdx.x];
-  const int64_t base = row_base(a, sp.x) + sp.y;
-  const int len = sp.z - sp.y;
-  const int n2 = next_pow2(len);
-  for (int i = threadIdx.x; i < n2; i += 256) keys[i] = i < len ? sc.pairs[base + i] : ~0ull;
-  __syncthreads();
-  bitonic_sort_lds(keys, n2, threadIdx.x, 256);
-  for (int i = threadIdx.x; i < len; i += 256) a.kv_perm[base + i] = (int32_t)(uint32_t)keys[i];
+  __shared__ uint16_t grp[kSpanCap];
+  __shared__ uint32_t start[kSubBuckets + 1];
+  __shared__ uint32_t fill[kSubBuckets];
+  __shared__ uint32_t wsum[8];
+  __shared__ uint32_t red[3];          // min / max of the ordered score bits, fullest sub-bucket
+  const int tid = threadIdx.x;
+  for (uint32_t w = blockIdx.x; w < min(sc.counters[0], (uint32_t)sc.max_spans); w += gridDim.x) {
+    const int4 sp = sc.spans[w];
+    const int64_t base = row_base(a, sp.x) + sp.y;
+    const int len = sp.z - sp.y;
+    if (tid == 0) { red[0] = 0xffffffffu; red[1] = 0u; red[2] = 0u; }
+    for (int i = tid; i < kSubBuckets; i += 256) fill[i] = 0;
+    __syncthreads();
+    uint32_t lo = 0xffffffffu, hi = 0u;
+    for (int i = tid; i < len; i += 256) {
+      const uint64_t k = sc.pairs[base + i];
+      keys[i] = k;
+      const uint32_t o = ~(uint32_t)(k >> 32);   // ordered score bits (ascending = ascending score)
+      lo = min(lo, o); hi = max(hi, o);
+    }
+    atomicMin(&red[0], lo);
+    atomicMax(&red[1], hi);
+    __syncthreads();
+    bool fallback = len < 64;
+    float fhi = 0.f, scale = 0.f;
+    if (!fallback) {
+      const float flo = ordered_to_float(red[0]);
+      fhi = ordered_to_float(red[1]);
+      const float range = fhi - flo;
+      scale = range > 0.f ? (float)kSubBuckets / range : 0.f;
+      // fine bucket of a key: descending score -> ascending sub-bucket (monotone in the key)
+      auto sub = [&](uint64_t k) {
+        const float f = ordered_to_float(~(uint32_t)(k >> 32));
+        return min(max((int)((fhi - f) * scale), 0), kSubBuckets - 1);
+      };
+      for (int i = tid; i < len; i += 256) atomicAdd(&fill[sub(keys[i])], 1u);
+      __syncthreads();
+      // exclusive scan of the 2048 counts: 8 per thread, then across threads
+      uint32_t cnt[8], run = 0, mx = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { cnt[e] = fill[8 * tid + e]; run += cnt[e]; mx = max(mx, cnt[e]); }
+      uint32_t incl = run;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t v = __shfl_up(incl, o);
+        if ((tid & 63) >= o) incl += v;
+      }
+      if ((tid & 63) == 63) wsum[tid >> 6] = incl;
+      atomicMax(&red[2], mx);
+      __syncthreads();
+      uint32_t woff = 0;
+      for (int k = 0; k < (tid >> 6); ++k) woff += wsum[k];
+      uint32_t ex = woff + incl - run;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { start[8 * tid + e] = ex; ex += cnt[e]; fill[8 * tid + e] = 0; }
+      if (tid == 255) start[kSubBuckets] = ex;
+      fallback = red[2] > (uint32_t)kSubMax;
+      __syncthreads();
+      if (!fallback) {
+        for (int i = tid; i < len; i += 256) {
+          const int sbk = sub(keys[i]);
+          grp[start[sbk] + atomicAdd(&fill[sbk], 1u)] = (uint16_t)i;
+        }
+        __syncthreads();
+        for (int p = tid; p < len; p += 256) {
+          const uint64_t k = keys[grp[p]];
+          const int sbk = sub(k);
+          const uint32_t s0 = start[sbk], s1 = start[sbk + 1];
+          uint32_t rank = s0;
+          for (uint32_t qd = s0; qd < s1; ++qd) rank += keys[grp[qd]] < k ? 1u : 0u;
+          a.kv_perm[base + rank] = (int32_t)(uint32_t)k;
+        }
+      }
+    }
+    if (fallback) {
+      const int n2 = next_pow2(len);
+      for (int i = len + tid; i < n2; i += 256) keys[i] = ~0ull;
+      __syncthreads();
+      bitonic_sort_lds(keys, n2, tid, 256);
+      for (int i = tid; i < len; i += 256) a.kv_perm[base + i] = (int32_t)(uint32_t)keys[i];
+    }
+    __syncthreads();
+  }
 }
 
 // Fallback: stable LSD radix sort (8 passes of 8 bits) of one oversized bucket by one
@@ -480,10 +632,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
   const int64_t rows = (int64_t)a.Z * a.H * a.N;
   const int G = a.H / a.Hkv;
 
-  {
-    const int64_t nthr = rows * kNBMax;
-    hipLaunchKernelGGL(init_kernel, dim3((unsigned)((nthr + 255) / 256)), dim3(256), 0, stream, sc, rows);
-  }
+  hipLaunchKernelGGL(init_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream, sc, rows);
   hipLaunchKernelGGL(kguide_kernel, dim3(a.Z * a.Hkv), dim3(256), 0, stream, a, sc);
   {
     int n2 = 1;
@@ -500,13 +649,27 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
   }
   if (a.N > 1) {
     const int RB = (G * a.N + 31) / 32;
-    const int nchunks = (a.L + kTokChunk - 1) / kTokChunk;
-    const dim3 grid((unsigned)((int64_t)a.Z * a.Hkv * RB * nchunks));
-    hipLaunchKernelGGL(score_kernel<0>, grid, dim3(256), 0, stream, a, sc);
-    hipLaunchKernelGGL(score_kernel<1>, grid, dim3(256), 0, stream, a, sc);
-    hipLaunchKernelGGL(scan_kernel, dim3((unsigned)rows), dim3(64), 0, stream, a, sc);
-    hipLaunchKernelGGL(score_kernel<2>, grid, dim3(256), 0, stream, a, sc);
-    hipLaunchKernelGGL(span_sort_kernel, dim3((unsigned)sc.max_spans), dim3(256), 0, stream, a, sc);
+    const int RBG = (RB + 3) / 4;
+    const int nchunks = (a.L + kChunk - 1) / kChunk;
+    const dim3 grid((unsigned)((int64_t)a.Z * a.Hkv * RBG * nchunks));
+    const size_t lds = (size_t)kSub * kKStride * 2 + 4 * 32 * (kNBMax / 2) * 4;
+    static bool attr2_set = false;
+    if (!attr2_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<0>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<1>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<2>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      attr2_set = true;
+    }
+    hipLaunchKernelGGL(score_kernel<0>, grid, dim3(256), lds, stream, a, sc);
+    hipLaunchKernelGGL(score_kernel<1>, grid, dim3(256), lds, stream, a, sc);
+    hipLaunchKernelGGL(scan_kernel, dim3((unsigned)rows), dim3(kNBMax), 0, stream, a, sc);
+    hipLaunchKernelGGL(score_kernel<2>, grid, dim3(256), lds, stream, a, sc);
+    const int64_t sort_grid = sc.max_spans < 8192 ? sc.max_spans : 8192;
+    hipLaunchKernelGGL(span_sort_kernel, dim3((unsigned)sort_grid), dim3(256), 0, stream, a, sc);
     hipLaunchKernelGGL(big_sort_kernel, dim3(kBigGrid), dim3(256), 0, stream, a, sc);
   }
   return hipGetLastError();
