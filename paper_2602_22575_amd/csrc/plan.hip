@@ -9,9 +9,11 @@
 //                        staged through LDS.  q_mean is split exactly into three bf16 terms
 //                        so that bf16 MFMA reproduces the fp32 x bf16 products exactly (fp32
 //                        accumulation).  The Argsort of a prefix row (up to L - S scores) is
-//                        a bucket sort on the score value, so the kernel runs three times
-//                        with different epilogues:
-//                          MODE 0  row min / max (+ optional s_K store)
+//                        a sample sort: buckets are delimited by splitters taken from a
+//                        sorted sample of the row, so their populations are balanced for
+//                        any score distribution.  The kernel runs three times with different
+//                        epilogues:
+//                          MODE 0  one sampled score per 64 tokens (+ optional s_K store)
 //                          MODE 1  per (row, 1024-token chunk) bucket counts, kept in LDS
 //                                  and written once per chunk (no global atomics)
 //                          MODE 2  scatter of (key, token) pairs to their bucket: global
@@ -20,6 +22,8 @@
 //                        Re-computing the scores costs K reads (0.27 GB at 128K, from the
 //                        last-level cache after the first pass) instead of a round trip of
 //                        the 0.53 GB score array.
+//   splitter_kernel      per prefix row: sorts the sample in LDS and keeps every
+//                        (sample size / buckets)-th value as a splitter.
 //   scan_kernel          per prefix row: cell offsets (bucket-major, chunk-minor) and the
 //                        list of spans (runs of consecutive buckets that fit the LDS sort).
 //   span_sort_kernel     sorts each span in LDS and writes the token indices at their
@@ -43,13 +47,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kD = 128;
-constexpr int kNBMax = 128;        // buckets per prefix row (upper bound)
-constexpr int kBucketAvg = 1024;   // target average bucket population
+constexpr int kNBMax = 64;         // buckets per prefix row (upper bound)
+constexpr int kBucketAvg = 2048;   // target average bucket population
+constexpr int kSampleStride = 64;  // one sampled score per this many tokens
+constexpr int kSplStride = kNBMax + 1;   // floats per row of splitters in LDS (odd: no bank pile-up)
 constexpr int kSpanCap = 4096;     // elements one span_sort workgroup sorts in LDS
 constexpr int kSubBuckets = 2048;  // fine buckets of the in-LDS sort
 constexpr int kSubMax = 64;        // a fuller sub-bucket sends the span to the bitonic fallback
 constexpr int kChunk = 1024;       // key tokens per score workgroup
-constexpr int kSub = 128;          // key tokens per LDS tile of the score kernel
+constexpr int kSub = 64;           // key tokens per LDS tile of the score kernel
 constexpr int kKStride = 136;      // bf16 elements per K row in LDS (272 B)
 constexpr int kBigGrid = 64;       // workgroups of the fallback sort
 
@@ -79,8 +85,8 @@ struct Scratch {
   float* kguide;      // [Z*Hkv*128]
   float* qmean;       // [Z*H*N*128]
   uint16_t* qsplit;   // [Z*H*N][3][128] bf16
-  uint32_t* rowmin;   // [Z*H*N] ordered-u32
-  uint32_t* rowmax;   // [Z*H*N]
+  float* samples;     // [Z*H*N][L/64] one score per 64 tokens of the row's prefix
+  float* splitters;   // [Z*H*N][kNBMax] descending; entries past the row's buckets are -inf
   uint16_t* chist;    // [Z*H*N][maxch][kNBMax] bucket counts per 1024-token chunk
   uint32_t* coffs;    // same shape: offset of the cell inside its row
   uint32_t* counters; // [0]=#spans [1]=#big spans [2]=error flag
@@ -107,8 +113,8 @@ static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S) {
   s.kguide = (float*)take((size_t)Z * Hkv * kD * 4);
   s.qmean = (float*)take((size_t)rows * kD * 4);
   s.qsplit = (uint16_t*)take((size_t)rows * 3 * kD * 2);
-  s.rowmin = (uint32_t*)take((size_t)rows * 4);
-  s.rowmax = (uint32_t*)take((size_t)rows * 4);
+  s.samples = (float*)take((size_t)rows * (L / kSampleStride) * 4);
+  s.splitters = (float*)take((size_t)rows * kNBMax * 4);
   s.chist = (uint16_t*)take((size_t)rows * s.maxch * kNBMax * 2);
   s.coffs = (uint32_t*)take((size_t)rows * s.maxch * kNBMax * 4);
   s.counters = (uint32_t*)take(64);
@@ -127,7 +133,6 @@ size_t plan_scratch_bytes(int Z, int H, int Hkv, int L, int S) {
 // ---------------------------------------------------------------------------------------
 __global__ void init_kernel(Scratch s, int64_t rows) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < rows) { s.rowmin[i] = 0xffffffffu; s.rowmax[i] = 0u; }
   if (i < 16) s.counters[i] = 0;
 }
 
@@ -257,6 +262,7 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t* Kt = reinterpret_cast<uint16_t*>(smem);                          // [kSub][kKStride]
   uint32_t* hist_all = reinterpret_cast<uint32_t*>(smem + kSub * kKStride * 2);  // [4][32][kNBMax/2]
+  float* spl_all = reinterpret_cast<float*>(hist_all + 4 * 32 * (kNBMax / 2));   // [4][32][kSplStride]
 
   const int G = a.H / a.Hkv;
   const int R = G * a.N;
@@ -298,15 +304,6 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
   const int64_t zh = (int64_t)z * a.H + g * G + rr / a.N;
   const int64_t row_id = zh * a.N + rr % a.N;
   const int64_t base = zh * kv_row_offset(a.N, a.S) + kv_row_offset(rr % a.N, a.S);
-  float rhi = 0.f, rscale = 0.f;
-  int rnb = 1;
-  if (MODE != 0 && lim > 0) {
-    const float lo = ordered_to_float(sc.rowmin[row_id]);
-    rhi = ordered_to_float(sc.rowmax[row_id]);
-    rnb = row_buckets(lim / a.S, a.S);
-    const float range = rhi - lo;
-    rscale = range > 0.f ? (float)rnb / range : 0.f;
-  }
   const int64_t cell = (row_id * sc.maxch + chunk) * kNBMax;
 
   // B fragments: 3 split terms x 8 contraction steps
@@ -321,28 +318,35 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
   }
 
   uint32_t* hist = hist_all + wave * 32 * (kNBMax / 2);   // two 16-bit counters per word
+  float* spl = spl_all + wave * 32 * kSplStride;           // this wavefront's rows' splitters
   if (MODE != 0) {
     for (int i = lane; i < 32 * (kNBMax / 2); i += 64) hist[i] = 0;
+    for (int i = 0; i < 32; ++i) {
+      const int r2 = min(32 * rb + i, R - 1);
+      const int64_t rid2 = ((int64_t)z * a.H + g * G + r2 / a.N) * a.N + r2 % a.N;
+      spl[i * kSplStride + lane] = sc.splitters[rid2 * kNBMax + lane];
+    }
   }
+  const float* myspl = spl + m_ * kSplStride;
+  const int samples_per_row = a.L / kSampleStride;
 
   // K tile loader: thread (c, q) moves 16-byte chunk c of rows q, q+16, ...
   const uint16_t* Kh = a.K + z * a.ks[0] + g * a.ks[1];
   const int c = tid & 15, q = tid >> 4;
-  u32x4 kreg[8];
+  u32x4 kreg[kSub / 16];
   auto load_tile = [&](int t0) {
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int s = 0; s < kSub / 16; ++s) {
       const int t = min(t0 + q + 16 * s, a.L - 1);
       kreg[s] = *reinterpret_cast<const u32x4*>(Kh + (int64_t)t * a.ks[2] + 8 * c);
     }
   };
   auto store_tile = [&]() {
 #pragma unroll
-    for (int s = 0; s < 8; ++s)
+    for (int s = 0; s < kSub / 16; ++s)
       *reinterpret_cast<u32x4*>(Kt + (q + 16 * s) * kKStride + 8 * c) = kreg[s];
   };
 
-  float vmin = INFINITY, vmax = -INFINITY;
   load_tile(t_begin);
   for (int t0 = t_begin; t0 < t_end; t0 += kSub) {
     __syncthreads();                       // previous tile fully consumed
@@ -351,7 +355,7 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
     if (t0 + kSub < t_end) load_tile(t0 + kSub);
     if (t0 < lim_wave) {
 #pragma unroll 1
-      for (int sb = 0; sb < 4; ++sb) {
+      for (int sb = 0; sb < kSub / 32; ++sb) {
         f32x16 acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
@@ -366,17 +370,24 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
 #pragma unroll
           for (int kk = 0; kk < 8; ++kk)
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], bq[tt][kk], acc, 0, 0, 0);
+        if (MODE == 0) {
+          // sample: one token of every 64, at a position that varies from block to block
+          const int blk = (t0 + 32 * sb) / kSampleStride;
+          const int off = ((blk * 37 + 11) & 63) - 32 * (sb & 1);   // offset inside this 32-token block
+          if (off >= 0 && off < 32 && ((off >> 2) & 1) == hh && t0 + 32 * sb < lim) {
+            const int idx = 4 * (off >> 3) + (off & 3);               // register holding that token
+            float v = acc[0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) v = idx == i ? acc[i] : v;
+            sc.samples[row_id * samples_per_row + blk] = v;
+          }
+        }
         // the four registers of a group are four consecutive tokens
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
           const int t = t0 + 32 * sb + 8 * i4 + 4 * hh;
           if (t < lim) {                   // lim is a multiple of 64: all four or none
             if (MODE == 0) {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                vmin = fminf(vmin, acc[4 * i4 + e]);
-                vmax = fmaxf(vmax, acc[4 * i4 + e]);
-              }
               if (a.s_k) {
                 const f32x4 v = {acc[4 * i4], acc[4 * i4 + 1], acc[4 * i4 + 2], acc[4 * i4 + 3]};
                 *reinterpret_cast<f32x4*>(a.s_k + base + t) = v;
@@ -385,8 +396,11 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
 #pragma unroll
               for (int e = 0; e < 4; ++e) {
                 const float sv = acc[4 * i4 + e];
-                int bk = (int)((rhi - sv) * rscale);
-                bk = min(max(bk, 0), rnb - 1);
+                // bucket = number of splitters above the score (descending splitters)
+                int bk = 0;
+#pragma unroll
+                for (int step = kNBMax / 2; step > 0; step >>= 1)
+                  bk += myspl[bk + step - 1] > sv ? step : 0;
                 const uint32_t inc = 1u << (16 * (bk & 1));
                 if (MODE == 1) {
                   atomicAdd(&hist[m_ * (kNBMax / 2) + (bk >> 1)], inc);
@@ -404,12 +418,6 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
       }
     }
   }
-  if (MODE == 0) {
-    if (lim > 0 && vmin <= vmax) {
-      atomicMin(&sc.rowmin[row_id], ordered_u32(vmin));
-      atomicMax(&sc.rowmax[row_id], ordered_u32(vmax));
-    }
-  }
   if (MODE == 1) {
     // counts of this (row block, chunk): one 256-byte row of kNBMax 16-bit counters per row
     __builtin_amdgcn_s_waitcnt(0);
@@ -419,9 +427,37 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
       if (row_limit(r2) > t_begin) {
         const int64_t zh2 = (int64_t)z * a.H + g * G + r2 / a.N;
         const int64_t cell2 = ((zh2 * a.N + r2 % a.N) * sc.maxch + chunk) * kNBMax;
-        reinterpret_cast<uint32_t*>(sc.chist + cell2)[lane] = hist[i * (kNBMax / 2) + lane];
+        if (lane < kNBMax / 2)
+          reinterpret_cast<uint32_t*>(sc.chist + cell2)[lane] = hist[i * (kNBMax / 2) + lane];
       }
     }
+  }
+}
+
+// Per prefix row: sort the sampled scores (descending) and keep every (ns / nb)-th one as a
+// splitter; bucket k of the row then holds the scores s with exactly k splitters above s.
+__global__ __launch_bounds__(256) void splitter_kernel(PlanArgs a, Scratch sc) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint64_t* keys = reinterpret_cast<uint64_t*>(smem);
+  const int64_t row_id = blockIdx.x;
+  const int n = (int)(row_id % a.N);
+  float* out = sc.splitters + row_id * kNBMax;
+  const int nb = n > 0 ? row_buckets(n, a.S) : 1;
+  if (nb == 1) {
+    if (threadIdx.x < kNBMax) out[threadIdx.x] = -INFINITY;
+    return;
+  }
+  const int ns = n * a.S / kSampleStride;
+  const int n2 = next_pow2(ns);
+  const float* smp = sc.samples + row_id * (a.L / kSampleStride);
+  for (int i = threadIdx.x; i < n2; i += 256) keys[i] = i < ns ? sort_key(smp[i], (uint32_t)i) : ~0ull;
+  __syncthreads();
+  bitonic_sort_lds(keys, n2, threadIdx.x, 256);
+  if (threadIdx.x < kNBMax) {
+    const int k = threadIdx.x + 1;     // splitter k separates buckets k-1 and k
+    float v = -INFINITY;
+    if (k < nb) v = ordered_to_float(~(uint32_t)(keys[(int64_t)k * ns / nb] >> 32));
+    out[threadIdx.x] = v;
   }
 }
 
@@ -652,7 +688,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
     const int RBG = (RB + 3) / 4;
     const int nchunks = (a.L + kChunk - 1) / kChunk;
     const dim3 grid((unsigned)((int64_t)a.Z * a.Hkv * RBG * nchunks));
-    const size_t lds = (size_t)kSub * kKStride * 2 + 4 * 32 * (kNBMax / 2) * 4;
+    const size_t lds = (size_t)kSub * kKStride * 2 + 4 * 32 * (kNBMax / 2) * 4 + 4 * 32 * kSplStride * 4;
     static bool attr2_set = false;
     if (!attr2_set) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<0>),
@@ -665,6 +701,11 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
       attr2_set = true;
     }
     hipLaunchKernelGGL(score_kernel<0>, grid, dim3(256), lds, stream, a, sc);
+    {
+      int ns2 = 1;
+      while (ns2 < a.L / kSampleStride) ns2 <<= 1;
+      hipLaunchKernelGGL(splitter_kernel, dim3((unsigned)rows), dim3(256), (size_t)ns2 * 8, stream, a, sc);
+    }
     hipLaunchKernelGGL(score_kernel<1>, grid, dim3(256), lds, stream, a, sc);
     hipLaunchKernelGGL(scan_kernel, dim3((unsigned)rows), dim3(kNBMax), 0, stream, a, sc);
     hipLaunchKernelGGL(score_kernel<2>, grid, dim3(256), lds, stream, a, sc);
