@@ -463,52 +463,60 @@ __global__ __launch_bounds__(256) void splitter_kernel(PlanArgs a, Scratch sc) {
 
 // Per prefix row: offsets of the (chunk, bucket) cells in bucket-major order, and the list
 // of spans handed to the sort kernels.
-__global__ __launch_bounds__(kNBMax) void scan_kernel(PlanArgs a, Scratch sc) {
+__global__ __launch_bounds__(4 * kNBMax) void scan_kernel(PlanArgs a, Scratch sc) {
+  __shared__ uint32_t part[4][kNBMax];   // counts of bucket b in chunk group q
   __shared__ uint32_t tot[kNBMax];
   __shared__ uint32_t bstart[kNBMax + 1];
   const int64_t row_id = blockIdx.x;
   const int n = (int)(row_id % a.N);
   if (n == 0) return;
-  const int b = threadIdx.x;
+  const int b = threadIdx.x % kNBMax, q = threadIdx.x / kNBMax;
   const int nb = row_buckets(n, a.S);
   const int nch = (n * a.S + kChunk - 1) / kChunk;
+  const int c0 = (nch * q) / 4, c1 = (nch * (q + 1)) / 4;   // this thread's chunk range
   const uint16_t* ch = sc.chist + row_id * sc.maxch * kNBMax;
   uint32_t* co = sc.coffs + row_id * sc.maxch * kNBMax;
   uint32_t t = 0;
   if (b < nb)
-    for (int c = 0; c < nch; ++c) t += ch[c * kNBMax + b];
-  tot[b] = t;
+    for (int c = c0; c < c1; ++c) t += ch[c * kNBMax + b];
+  part[q][b] = t;
   __syncthreads();
-  if (b == 0) {
-    uint32_t off = 0, span_begin = 0;
+  if (q == 0) tot[b] = part[0][b] + part[1][b] + part[2][b] + part[3][b];
+  __syncthreads();
+  __shared__ int2 lspan[kNBMax + 1], lbig[kNBMax];   // this row's spans, gathered locally
+  __shared__ uint32_t nsp[2], gbase[2];
+  if (threadIdx.x == 0) {
+    uint32_t off = 0, span_begin = 0, ns = 0, nbig = 0;
     for (int k = 0; k < nb; ++k) {
       const uint32_t cnt = tot[k];
       bstart[k] = off;
       if (cnt > (uint32_t)kSpanCap) {
-        if (off > span_begin) {
-          const uint32_t s = atomicAdd(&sc.counters[0], 1u);
-          if ((int64_t)s < sc.max_spans) sc.spans[s] = make_int4((int)row_id, (int)span_begin, (int)off, 0);
-        }
-        const uint32_t s = atomicAdd(&sc.counters[1], 1u);
-        if ((int64_t)s < sc.max_spans) sc.bigspans[s] = make_int4((int)row_id, (int)off, (int)(off + cnt), 0);
+        if (off > span_begin) lspan[ns++] = make_int2((int)span_begin, (int)off);
+        lbig[nbig++] = make_int2((int)off, (int)(off + cnt));
         span_begin = off + cnt;
       } else if (off + cnt - span_begin > (uint32_t)kSpanCap) {
-        const uint32_t s = atomicAdd(&sc.counters[0], 1u);
-        if ((int64_t)s < sc.max_spans) sc.spans[s] = make_int4((int)row_id, (int)span_begin, (int)off, 0);
+        lspan[ns++] = make_int2((int)span_begin, (int)off);
         span_begin = off;
       }
       off += cnt;
     }
-    if (off > span_begin) {
-      const uint32_t s = atomicAdd(&sc.counters[0], 1u);
-      if ((int64_t)s < sc.max_spans) sc.spans[s] = make_int4((int)row_id, (int)span_begin, (int)off, 0);
-    }
+    if (off > span_begin) lspan[ns++] = make_int2((int)span_begin, (int)off);
     if (off != (uint32_t)(n * a.S)) sc.counters[2] = 2u;
+    nsp[0] = ns; nsp[1] = nbig;
+    // one reservation per list instead of one (slow, serialised) atomic per span
+    gbase[0] = ns ? atomicAdd(&sc.counters[0], ns) : 0u;
+    gbase[1] = nbig ? atomicAdd(&sc.counters[1], nbig) : 0u;
   }
+  __syncthreads();
+  if (threadIdx.x < nsp[0] && (int64_t)(gbase[0] + threadIdx.x) < sc.max_spans)
+    sc.spans[gbase[0] + threadIdx.x] = make_int4((int)row_id, lspan[threadIdx.x].x, lspan[threadIdx.x].y, 0);
+  if (threadIdx.x < nsp[1] && (int64_t)(gbase[1] + threadIdx.x) < sc.max_spans)
+    sc.bigspans[gbase[1] + threadIdx.x] = make_int4((int)row_id, lbig[threadIdx.x].x, lbig[threadIdx.x].y, 0);
   __syncthreads();
   if (b < nb) {
     uint32_t running = bstart[b];
-    for (int c = 0; c < nch; ++c) {
+    for (int k = 0; k < q; ++k) running += part[k][b];
+    for (int c = c0; c < c1; ++c) {
       co[c * kNBMax + b] = running;
       running += ch[c * kNBMax + b];
     }
@@ -521,73 +529,86 @@ __device__ inline int64_t row_base(const PlanArgs& a, int64_t row_id) {
   return zh * kv_row_offset(a.N, a.S) + kv_row_offset(n, a.S);
 }
 
-__global__ __launch_bounds__(256) void span_sort_kernel(PlanArgs a, Scratch sc) {
+constexpr int kSortThreads = 1024;
+constexpr int kPerThread = kSubBuckets / kSortThreads;   // sub-bucket counters scanned per thread
+
+__global__ __launch_bounds__(kSortThreads) void span_sort_kernel(PlanArgs a, Scratch sc) {
   __shared__ uint64_t keys[kSpanCap];
   __shared__ uint16_t grp[kSpanCap];
   __shared__ uint32_t start[kSubBuckets + 1];
   __shared__ uint32_t fill[kSubBuckets];
-  __shared__ uint32_t wsum[8];
+  __shared__ uint32_t wsum[kSortThreads / 64];
   __shared__ uint32_t red[3];          // min / max of the ordered score bits, fullest sub-bucket
   const int tid = threadIdx.x;
-  for (uint32_t w = blockIdx.x; w < min(sc.counters[0], (uint32_t)sc.max_spans); w += gridDim.x) {
+  const uint32_t nspans = min(sc.counters[0], (uint32_t)sc.max_spans);
+  for (uint32_t w = blockIdx.x; w < nspans; w += gridDim.x) {
     const int4 sp = sc.spans[w];
     const int64_t base = row_base(a, sp.x) + sp.y;
     const int len = sp.z - sp.y;
     if (tid == 0) { red[0] = 0xffffffffu; red[1] = 0u; red[2] = 0u; }
-    for (int i = tid; i < kSubBuckets; i += 256) fill[i] = 0;
+    for (int i = tid; i < kSubBuckets; i += kSortThreads) fill[i] = 0;
     __syncthreads();
     uint32_t lo = 0xffffffffu, hi = 0u;
-    for (int i = tid; i < len; i += 256) {
+    for (int i = tid; i < len; i += kSortThreads) {
       const uint64_t k = sc.pairs[base + i];
       keys[i] = k;
       const uint32_t o = ~(uint32_t)(k >> 32);   // ordered score bits (ascending = ascending score)
       lo = min(lo, o); hi = max(hi, o);
     }
-    atomicMin(&red[0], lo);
-    atomicMax(&red[1], hi);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      lo = min(lo, (uint32_t)__shfl_xor((int)lo, o));
+      hi = max(hi, (uint32_t)__shfl_xor((int)hi, o));
+    }
+    if ((tid & 63) == 0) { atomicMin(&red[0], lo); atomicMax(&red[1], hi); }
     __syncthreads();
     bool fallback = len < 64;
-    float fhi = 0.f, scale = 0.f;
     if (!fallback) {
       const float flo = ordered_to_float(red[0]);
-      fhi = ordered_to_float(red[1]);
+      const float fhi = ordered_to_float(red[1]);
       const float range = fhi - flo;
-      scale = range > 0.f ? (float)kSubBuckets / range : 0.f;
+      const float scale = range > 0.f ? (float)kSubBuckets / range : 0.f;
       // fine bucket of a key: descending score -> ascending sub-bucket (monotone in the key)
       auto sub = [&](uint64_t k) {
         const float f = ordered_to_float(~(uint32_t)(k >> 32));
         return min(max((int)((fhi - f) * scale), 0), kSubBuckets - 1);
       };
-      for (int i = tid; i < len; i += 256) atomicAdd(&fill[sub(keys[i])], 1u);
+      for (int i = tid; i < len; i += kSortThreads) atomicAdd(&fill[sub(keys[i])], 1u);
       __syncthreads();
-      // exclusive scan of the 2048 counts: 8 per thread, then across threads
-      uint32_t cnt[8], run = 0, mx = 0;
+      // exclusive scan of the sub-bucket counts: kPerThread per thread, then across threads
+      uint32_t cnt[kPerThread], run = 0, mx = 0;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { cnt[e] = fill[8 * tid + e]; run += cnt[e]; mx = max(mx, cnt[e]); }
+      for (int e = 0; e < kPerThread; ++e) {
+        cnt[e] = fill[kPerThread * tid + e]; run += cnt[e]; mx = max(mx, cnt[e]);
+      }
       uint32_t incl = run;
 #pragma unroll
       for (int o = 1; o < 64; o <<= 1) {
         const uint32_t v = __shfl_up(incl, o);
         if ((tid & 63) >= o) incl += v;
       }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o));
       if ((tid & 63) == 63) wsum[tid >> 6] = incl;
-      atomicMax(&red[2], mx);
+      if ((tid & 63) == 0) atomicMax(&red[2], mx);
       __syncthreads();
       uint32_t woff = 0;
       for (int k = 0; k < (tid >> 6); ++k) woff += wsum[k];
       uint32_t ex = woff + incl - run;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { start[8 * tid + e] = ex; ex += cnt[e]; fill[8 * tid + e] = 0; }
-      if (tid == 255) start[kSubBuckets] = ex;
+      for (int e = 0; e < kPerThread; ++e) {
+        start[kPerThread * tid + e] = ex; ex += cnt[e]; fill[kPerThread * tid + e] = 0;
+      }
+      if (tid == kSortThreads - 1) start[kSubBuckets] = ex;
       fallback = red[2] > (uint32_t)kSubMax;
       __syncthreads();
       if (!fallback) {
-        for (int i = tid; i < len; i += 256) {
+        for (int i = tid; i < len; i += kSortThreads) {
           const int sbk = sub(keys[i]);
           grp[start[sbk] + atomicAdd(&fill[sbk], 1u)] = (uint16_t)i;
         }
         __syncthreads();
-        for (int p = tid; p < len; p += 256) {
+        for (int p = tid; p < len; p += kSortThreads) {
           const uint64_t k = keys[grp[p]];
           const int sbk = sub(k);
           const uint32_t s0 = start[sbk], s1 = start[sbk + 1];
@@ -599,10 +620,10 @@ __global__ __launch_bounds__(256) void span_sort_kernel(PlanArgs a, Scratch sc) 
     }
     if (fallback) {
       const int n2 = next_pow2(len);
-      for (int i = len + tid; i < n2; i += 256) keys[i] = ~0ull;
+      for (int i = len + tid; i < n2; i += kSortThreads) keys[i] = ~0ull;
       __syncthreads();
-      bitonic_sort_lds(keys, n2, tid, 256);
-      for (int i = tid; i < len; i += 256) a.kv_perm[base + i] = (int32_t)(uint32_t)keys[i];
+      bitonic_sort_lds(keys, n2, tid, kSortThreads);
+      for (int i = tid; i < len; i += kSortThreads) a.kv_perm[base + i] = (int32_t)(uint32_t)keys[i];
     }
     __syncthreads();
   }
@@ -707,10 +728,10 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
       hipLaunchKernelGGL(splitter_kernel, dim3((unsigned)rows), dim3(256), (size_t)ns2 * 8, stream, a, sc);
     }
     hipLaunchKernelGGL(score_kernel<1>, grid, dim3(256), lds, stream, a, sc);
-    hipLaunchKernelGGL(scan_kernel, dim3((unsigned)rows), dim3(kNBMax), 0, stream, a, sc);
+    hipLaunchKernelGGL(scan_kernel, dim3((unsigned)rows), dim3(4 * kNBMax), 0, stream, a, sc);
     hipLaunchKernelGGL(score_kernel<2>, grid, dim3(256), lds, stream, a, sc);
     const int64_t sort_grid = sc.max_spans < 8192 ? sc.max_spans : 8192;
-    hipLaunchKernelGGL(span_sort_kernel, dim3((unsigned)sort_grid), dim3(256), 0, stream, a, sc);
+    hipLaunchKernelGGL(span_sort_kernel, dim3((unsigned)sort_grid), dim3(kSortThreads), 0, stream, a, sc);
     hipLaunchKernelGGL(big_sort_kernel, dim3(kBigGrid), dim3(256), 0, stream, a, sc);
   }
   return hipGetLastError();
