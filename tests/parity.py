@@ -3,9 +3,11 @@
 Integer results are compared exactly wherever the fp64 oracle says the answer is
 separable from its neighbours, and by admissible-set membership inside a guard band:
 
-  scores      |s_gpu - s_orc| <= e := SCORE_TOL * sum_d |a_d b_d| + 1e-6: a 128-term fp32
+  scores      |s_gpu - s_orc| <= e := SCORE_TOL * sum_d |a_d b_d| + 1e-6.  A 128-term fp32
               dot product of exactly representable products has a worst-case error of
-              128 * 2^-24 = 7.6e-6 of that sum and a typical one of ~1e-6.
+              128 * 2^-24 = 7.6e-6 of that sum; the MFMA accumulation measures <= 2.4e-7 of
+              it on every workload up to 128K (printed as max_sk_err_over_bound), so 1e-6
+              leaves a 4x margin while keeping the near-tie runs below short.
   argsort     (a) perm_gpu == stable_argsort_desc(scores_gpu), bit-exact: checks the sort
                   and its tie-break on the very keys the GPU sorted;
               (b) perm_gpu == perm_orc at every rank outside an oracle near-tie run
@@ -27,7 +29,7 @@ import numpy as np
 from oracle import s2o_oracle as orc
 from paper_2602_22575_amd import inputs
 
-SCORE_TOL = 4e-6
+SCORE_TOL = 1e-6
 G_STOP = 1e-3
 O_MAX_ABS = 2e-2
 O_REL_MSE = 1e-4
@@ -63,47 +65,47 @@ def check_perm_against_oracle(perm_gpu, perm_orc, s_orc, tol):
     return int(diff.size), nruns
 
 
-def check_plan(w, Qb, Kb, plan_gpu, heads=None, exact=False):
+def check_plan(w, Qb, Kb, plan_gpu, heads=None, exact=False, segments=None):
     """plan_gpu: dict of numpy arrays (q_perm, kv_perm, s_q, s_k, q_mean, k_guide) from
-    the HIP path.  Returns a stats dict."""
-    Q, K = to_f64(Qb), to_f64(Kb)
-    if heads is not None:
-        G = w.G
-        kvh = sorted({h // G for h in heads})
-        assert [h // G for h in heads] == sorted(h // G for h in heads)
-    ref = orc.plan(Q, K, w.S)
+    the HIP path.  The oracle is run head by head (one query head + its KV head at a time).
+    Returns a stats dict."""
     S, N = w.S, w.N
-    stats = dict(q_mismatch=0, q_runs=0, kv_mismatch=0, kv_runs=0, rows=0)
-    # pooled vectors
-    np.testing.assert_allclose(plan_gpu["k_guide"], ref["k_guide"], rtol=0, atol=2e-6 * np.abs(K).max())
-    np.testing.assert_allclose(plan_gpu["q_mean"], ref["q_mean"], rtol=0, atol=2e-6 * np.abs(Q).max())
+    stats = dict(q_mismatch=0, q_runs=0, kv_mismatch=0, kv_runs=0, rows=0, max_sk_err_over_bound=0.0)
     for z in range(w.Z):
         for h in (range(w.H) if heads is None else heads):
             g = h // w.G
-            for n in range(N):
+            Q = to_f64(Qb[z:z + 1, h:h + 1])
+            K = to_f64(Kb[z:z + 1, g:g + 1])
+            ref = orc.plan(Q, K, S)
+            np.testing.assert_allclose(plan_gpu["k_guide"][z, g], ref["k_guide"][0, 0], rtol=0,
+                                       atol=2e-6 * np.abs(K).max())
+            np.testing.assert_allclose(plan_gpu["q_mean"][z, h], ref["q_mean"][0, 0], rtol=0,
+                                       atol=2e-6 * np.abs(Q).max())
+            for n in (range(N) if segments is None else segments):
                 # s_Q and Q_perm
                 sq_g = plan_gpu["s_q"][z, h, n]
-                bound = np.abs(Q[z, h, n * S:(n + 1) * S]) @ np.abs(ref["k_guide"][z, g])
-                assert np.all(np.abs(sq_g - ref["s_q"][z, h, n]) <= score_tol(bound)), \
-                    f"s_Q error {np.abs(sq_g - ref['s_q'][z, h, n]).max()} (h={h}, n={n})"
+                sq_o = ref["s_q"][0, 0, n]
+                bound = np.abs(Q[0, 0, n * S:(n + 1) * S]) @ np.abs(ref["k_guide"][0, 0])
+                assert np.all(np.abs(sq_g - sq_o) <= score_tol(bound)), \
+                    f"s_Q error {np.abs(sq_g - sq_o).max()} (h={h}, n={n})"
                 qp = plan_gpu["q_perm"][z, h, n]
                 assert np.array_equal(qp, np.argsort(-sq_g, kind="stable")), "Q_perm is not the stable argsort of s_Q"
-                mm, runs = check_perm_against_oracle(qp, ref["q_perm"][z, h, n], ref["s_q"][z, h, n],
-                                                     score_tol(bound))
+                mm, runs = check_perm_against_oracle(qp, ref["q_perm"][0, 0, n], sq_o, score_tol(bound))
                 stats["q_mismatch"] += mm
                 stats["q_runs"] += runs
                 if n == 0:
                     continue
                 o = orc.kv_row_offset(n, S)
                 sk_g = plan_gpu["s_k"][z, h, o:o + n * S]
-                sk_o = ref["s_k"][z, h, o:o + n * S]
-                bound = np.abs(K[z, g, :n * S]) @ np.abs(ref["q_mean"][z, h, n])
-                assert np.all(np.abs(sk_g - sk_o) <= score_tol(bound)), \
-                    f"s_K error {np.abs(sk_g - sk_o).max()} (h={h}, n={n})"
+                sk_o = ref["s_k"][0, 0, o:o + n * S]
+                bound = np.abs(K[0, 0, :n * S]) @ np.abs(ref["q_mean"][0, 0, n])
+                err = np.abs(sk_g - sk_o)
+                stats["max_sk_err_over_bound"] = max(stats["max_sk_err_over_bound"], float((err / bound).max()))
+                assert np.all(err <= score_tol(bound)), f"s_K error {err.max()} (h={h}, n={n})"
                 kp = plan_gpu["kv_perm"][z, h, o:o + n * S]
                 assert np.array_equal(kp, np.argsort(-sk_g, kind="stable")), \
                     f"KV_perm is not the stable argsort of s_K (h={h}, n={n})"
-                mm, runs = check_perm_against_oracle(kp, ref["kv_perm"][z, h, o:o + n * S], sk_o,
+                mm, runs = check_perm_against_oracle(kp, ref["kv_perm"][0, 0, o:o + n * S], sk_o,
                                                      score_tol(bound))
                 stats["kv_mismatch"] += mm
                 stats["kv_runs"] += runs
@@ -140,41 +142,41 @@ def check_counts(gain_row, tau, stop_mode, computed, skipped):
 
 def check_attention(w, Qb, Kb, Vb, q_perm, kv_perm, tau, stop_mode, O_gpu_bits, computed, skipped,
                     heads=None, segments=None, gains=None, use_q_perm=True):
-    """Compares one s2o_attention result with the oracle run on the same maps.  Returns
-    stats (robust/ambiguous tile counts, max-abs and relative MSE of O)."""
-    Q, K, V = to_f64(Qb), to_f64(Kb), to_f64(Vb)
+    """Compares one s2o_attention result with the oracle run on the same maps, one query head
+    (with its KV head) at a time.  Returns stats (robust/ambiguous tile counts, max-abs and
+    relative MSE of O) and the gain profiles (reusable for another tau)."""
     S, N, BM, BN = w.S, w.N, w.BM, w.BN
     TJ = S // BM
-    if not use_q_perm:
-        q_perm = orc.identity_maps(w.Z, w.H, w.L, S)[0]
     hs = list(range(w.H)) if heads is None else list(heads)
     ns = list(range(N)) if segments is None else list(segments)
-    if gains is None:
-        gains = orc.gain_profile(Q, K, V, q_perm, kv_perm, S, BM, BN, stop_mode=stop_mode,
-                                 heads=hs, segments=ns)
+    gains = {} if gains is None else gains
     robust = ambiguous = 0
+    max_abs = num = den = 0.0
     for z in range(w.Z):
         for h in hs:
+            g = h // w.G
+            Q, K, V = to_f64(Qb[z:z + 1, h:h + 1]), to_f64(Kb[z:z + 1, g:g + 1]), to_f64(Vb[z:z + 1, g:g + 1])
+            qp = q_perm[z:z + 1, h:h + 1] if use_q_perm else orc.identity_maps(1, 1, w.L, S)[0]
+            kp = kv_perm[z:z + 1, h:h + 1]
+            if (z, h) not in gains:
+                gains[(z, h)] = orc.gain_profile(Q, K, V, qp, kp, S, BM, BN, stop_mode=stop_mode, segments=ns)
+            gz = gains[(z, h)]
             for n in ns:
                 for j in range(TJ):
                     c = int(computed[z, h, n * TJ + j]); s = int(skipped[z, h, n * TJ + j])
                     if n == 0:
                         assert (c, s) == (0, 0)
                         continue
-                    if check_counts(gains[(z, h, n)][j], tau, stop_mode, c, s):
+                    if check_counts(gz[(0, 0, n)][j], tau, stop_mode, c, s):
                         robust += 1
                     else:
                         ambiguous += 1
-    O_ref, _, _ = orc.attention(Q, K, V, q_perm, kv_perm, S, BM, BN, tau=0.0, stop_mode=stop_mode,
-                                forced_computed=computed, heads=hs, segments=ns)
-    O_gpu = to_f64(O_gpu_bits)
-    max_abs = 0.0
-    num = den = 0.0
-    for z in range(w.Z):
-        for h in hs:
+            O_ref, _, _ = orc.attention(Q, K, V, qp, kp, S, BM, BN, tau=0.0, stop_mode=stop_mode,
+                                        forced_computed=computed[z:z + 1, h:h + 1], segments=ns)
+            O_gpu = to_f64(O_gpu_bits[z, h])
             for n in ns:
-                a = O_gpu[z, h, n * S:(n + 1) * S]
-                b = O_ref[z, h, n * S:(n + 1) * S]
+                a = O_gpu[n * S:(n + 1) * S]
+                b = O_ref[0, 0, n * S:(n + 1) * S]
                 max_abs = max(max_abs, float(np.abs(a - b).max()))
                 num += float(((a - b) ** 2).sum())
                 den += float((b ** 2).sum())
@@ -187,7 +189,10 @@ def check_attention(w, Qb, Kb, Vb, q_perm, kv_perm, tau, stop_mode, O_gpu_bits, 
 def pick_tau(gains, nominal, margin=5 * G_STOP):
     """Nearest threshold >= nominal that no evaluated gain comes within `margin` (relative)
     of, so that every stop decision is robust and counts can be compared exactly."""
-    allg = np.concatenate([g[np.isfinite(g)].ravel() for g in gains.values() if g.size])
+    flat = []
+    for g in gains.values():
+        flat.extend(g.values() if isinstance(g, dict) else [g])
+    allg = np.concatenate([g[np.isfinite(g)].ravel() for g in flat if g.size])
     tau = nominal
     for _ in range(1000):
         if not np.any(np.abs(allg / tau - 1.0) <= margin):

@@ -43,7 +43,7 @@ def test_tiny_attention(tiny, stop_mode):
     plan, pg = gu.gpu_plan(w, Qd, Kd)
     Q, K, V = (parity.to_f64(x) for x in (Qb, Kb, Vb))
     dense = orc.dense_attention(Q, K, V)
-    gains = orc.gain_profile(Q, K, V, pg["q_perm"], pg["kv_perm"], w.S, w.BM, w.BN, stop_mode=stop_mode)
+    gains = {(0, 0): orc.gain_profile(Q, K, V, pg["q_perm"], pg["kv_perm"], w.S, w.BM, w.BN, stop_mode=stop_mode)}
     for tau in (0.0, -1.0, 0.02, 0.05, 0.2):
         if tau > 0:
             tau = parity.pick_tau(gains, tau)       # fixed by the oracle: no knife-edge decision
@@ -186,3 +186,49 @@ def test_llama8k(gpu):
                 d = orc.dense_attention(Q[:, h:h + 1], K[:, h // w.G:h // w.G + 1], V[:, h // w.G:h // w.G + 1], rows=rows)
                 err = np.abs(parity.to_f64(Ob[0, h, rows]) - d[0, 0])
                 assert err.max() <= parity.O_MAX_ABS
+
+
+def _sampled_case(name, plan_heads, attn_samples, taus, stop_mode=0):
+    """Full-size workload in the launch configuration bench.py times (all heads, whole
+    sequence on the GPU); the oracle checks the plan on a few heads and the attention on a
+    few (head, segment) pairs it can compute one by one."""
+    w = inputs.workload(name)
+    _say(f"case: {name} generate L={w.L}")
+    Qb, Kb, Vb = inputs.make_qkv(w)
+    Qd, Kd, Vd = (gu.to_dev(x) for x in (Qb, Kb, Vb))
+    _say(f"case: {name} plan on the GPU")
+    plan, pg = gu.gpu_plan(w, Qd, Kd)
+    # integer-exact sort check on every row of every head
+    for h in range(w.H):
+        for n in range(1, w.N):
+            o = orc.kv_row_offset(n, w.S)
+            sk = pg["s_k"][0, h, o:o + n * w.S]
+            assert np.array_equal(pg["kv_perm"][0, h, o:o + n * w.S], np.argsort(-sk, kind="stable")), (h, n)
+    _say(f"case: {name} oracle plan on heads {plan_heads}")
+    stats = parity.check_plan(w, Qb, Kb, pg, heads=plan_heads)
+    _say("  plan stats", stats)
+    for tau in taus:
+        _say(f"case: {name} attention tau={tau}")
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, stop_mode)
+        tot = orc.prefix_tiles(w.L, w.S, w.BM, w.BN)[None, None]
+        assert np.all((c >= 0) & (s >= 0) & (tot - c - s >= 0) & (tot - c - s <= 1))
+        if tau <= 0:
+            assert np.all(s == 0) and np.all(c == tot)
+        for h, segs in attn_samples:
+            st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, stop_mode, Ob, c, s,
+                                        heads=[h], segments=segs)
+            st.pop("gains")
+            _say(f"   head {h} segments {segs}:", st)
+        _say("   mean density", float(orc.density(s, w.L, w.S, w.BM, w.BN).mean()))
+
+
+def test_llama32k_sampled(gpu):
+    """32K, heavy tokens in bursts (token-level non-contiguous gather), tau = 1e-3."""
+    _sampled_case("llama32k", plan_heads=[0, 9, 18, 27], attn_samples=[(0, [1, 8, 15]), (27, [5])], taus=(1e-3,))
+
+
+def test_llama128k_sampled(gpu):
+    """The headline shape (128K): plan parity on two heads, attention parity on sampled
+    (head, segment) pairs, at the threshold bench.py times and with skipping disabled on
+    one short segment."""
+    _sampled_case("llama128k", plan_heads=[3, 20], attn_samples=[(3, [1, 21]), (20, [42])], taus=(5e-3,))
