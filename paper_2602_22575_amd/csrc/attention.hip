@@ -23,7 +23,11 @@
 // l, the element [row 8*(i/4) + 4*hh + i%4][column m].  The B operand of the PV product takes
 // registers 8*kk..8*kk+7 of an S^T block as its 8 contraction slots, so slot (hh, jj) is key
 // 16*kk + 8*(jj/4) + 4*hh + jj%4 of the 32-key block.  K and V tiles sit row-major (token
-// rows) in LDS.  The K operand is a plain 16-byte read of a row; the V^T operand is read
+// rows) in LDS, written there directly by global_load_lds (no staging registers): a
+// wavefront instruction deposits 4 gathered rows as 1 KB, lane l at byte 16*l, so rows
+// cannot be padded; bank conflicts are avoided by an XOR swizzle instead (lane l fetches
+// chunk (l%16) ^ swz(row) of its row, swz(r) = 2*(r%8) + (r/8)%2).
+// The K operand is a plain 16-byte read of a row; the V^T operand is read
 // with the transposing LDS load ds_read_b64_tr_b16: within each group of 16 lanes, lane i
 // receives element (i % 4) of the four 8-byte rows pointed to by lanes i/4, 4 + i/4, 8 + i/4
 // and 12 + i/4, so pointing lane r of a group at (key slot r/4, dims 4*(r%4)..+3) hands every
@@ -45,10 +49,10 @@ constexpr int kBM = 64;          // query tile (two wavefronts)
 constexpr int kTilesPerWg = 4;   // query tiles per workgroup
 constexpr int kWaves = 2 * kTilesPerWg;
 constexpr int kThreads = 64 * kWaves;
-constexpr int kKsStride = 136;   // bf16 elements per K row in LDS (272 B: conflict-free 16 B reads)
-constexpr int kVtStride = 160;   // bf16 elements per V row in LDS (320 B: conflict-free transposing reads)
-constexpr int kKsElems = kBN * kKsStride;
-constexpr int kVtElems = kBN * kVtStride;
+constexpr int kRowElems = kD;    // K and V rows sit unpadded in LDS (256 B); the sixteen 16-byte
+                                 // chunks of row r are stored at slot (chunk ^ swz(r)) instead
+constexpr int kKsElems = kBN * kRowElems;
+constexpr int kVtElems = kBN * kRowElems;
 constexpr size_t kAttnLds = (size_t)(2 * kKsElems + 3 * kVtElems) * 2 + 256;
 
 __device__ inline int wave_max_i32(int v) {
@@ -138,47 +142,65 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   const int nloc = wg_pmax / kBN + 1;          // own-segment key tiles this workgroup needs
   const int ntiles = nloc + nK;
 
-  // ---- loader: wavefronts 0-3 move K, 4-7 move V; thread (c, gq) moves 16-byte chunk c of
-  // key slots 4*gq .. 4*gq+3
-  const int ltid = tid & 255;
-  const bool loads_v = tid >= 256;
-  const int c = ltid & 15, gq = ltid >> 4;
+  // ---- loader: wavefronts 0-3 move K, 4-7 move V, 4 groups of 4 rows each per tile; in a
+  // group lane l moves one 16-byte chunk of row 4*group + l/16 straight into LDS
+  auto swz = [](int r) { return ((r & 7) << 1) | ((r >> 3) & 1); };
+  const bool loads_v = wave >= 4;
   const uint16_t* src = loads_v ? Vh : Kh;
   const int64_t src_stride = loads_v ? a.vs[2] : a.ks[2];
-  u32x4 lreg[4];
-  auto load_tile = [&](int it) {
-    int tok[4];
-    if (it < nloc) {
+  typedef __attribute__((address_space(1))) void gvoid;
+  typedef __attribute__((address_space(3))) void lvoid;
+  // token indices of the tile after the one being fetched are read one step ahead, so that a
+  // fetch never waits for its own index loads
+  int tokn[4];
+  auto load_index = [&](int it) {
+    int ld[4] = {0, 0, 0, 0};
+    if (nK > 0) {                      // one uniform branch; the loads themselves are unconditional
+      const int pt = min(max(it - nloc, 0), nK - 1);
 #pragma unroll
-      for (int s = 0; s < 4; ++s) tok[s] = nS + it * kBN + 4 * gq + s;
-    } else {
-      const int4 t4 = *reinterpret_cast<const int4*>(kvrow + (int64_t)(it - nloc) * kBN + 4 * gq);
-      tok[0] = t4.x; tok[1] = t4.y; tok[2] = t4.z; tok[3] = t4.w;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) tok[s] = min(max(tok[s], 0), a.L - 1);
+      for (int gi = 0; gi < 4; ++gi)
+        ld[gi] = kvrow[(int64_t)pt * kBN + 16 * (wave & 3) + 4 * gi + (lane >> 4)];
     }
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      lreg[s] = *reinterpret_cast<const u32x4*>(src + (int64_t)tok[s] * src_stride + 8 * c);
+    for (int gi = 0; gi < 4; ++gi)
+      tokn[gi] = it < nloc ? nS + it * kBN + 16 * (wave & 3) + 4 * gi + (lane >> 4) : ld[gi];
   };
-  auto store_tile = [&](int it) {       // K tiles alternate between 2 buffers, V tiles between 3
+  auto load_tile = [&](int it) {       // K tiles alternate between 2 buffers, V tiles between 3
     uint16_t* dst = loads_v ? Vt + (it % 3) * kVtElems : Ks + (it & 1) * kKsElems;
-    const int stride = loads_v ? kVtStride : kKsStride;
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      *reinterpret_cast<u32x4*>(dst + (4 * gq + s) * stride + 8 * c) = lreg[s];
+    for (int gi = 0; gi < 4; ++gi) {
+      const int row = 16 * (wave & 3) + 4 * gi + (lane >> 4);
+      const int tok = min(max(tokn[gi], 0), a.L - 1);
+      const uint16_t* gp = src + (int64_t)tok * src_stride + 8 * ((lane & 15) ^ swz(row));
+      __builtin_amdgcn_global_load_lds((const gvoid*)gp, (lvoid*)(dst + (16 * (wave & 3) + 4 * gi) * kRowElems),
+                                       16, 0, 0);
+    }
+    load_index(it + 1);
   };
+  // K operand: row 32*nb + m_, chunk 2*kk + hh -> per-lane byte offsets for the 8 steps
+  int koff[8];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) koff[kk] = m_ * kRowElems + 8 * ((2 * kk + hh) ^ swz(m_));
   // transposing read of 4 keys x this lane's dimension: lane (group g16 = lane/16, r = lane%16)
-  // points at key slot r/4 (+ 4 for the upper lane half), dims 16*(g16&1) + 4*(r%4)
-  const int vt_lane_off = ((lane & 15) >> 2) * kVtStride + 4 * (lane >> 5) * kVtStride
-                          + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  // points at key slot r/4 (+ 4 for the upper lane half), dims 16*(g16&1) + 4*(r%4); the row's
+  // swizzle depends on the lane and on which 8-key half (a) of the 16-key step is read
   typedef short i16x4 __attribute__((ext_vector_type(4)));
   typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+  int voff[4][2];
+  {
+    const int rl = ((lane & 15) >> 2) + 4 * (lane >> 5);          // row inside the 8-key half
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int a8 = 0; a8 < 2; ++a8) {
+        const int chunk = 4 * db + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+        voff[db][a8] = (rl + 8 * a8) * kRowElems + 8 * (chunk ^ swz(rl + 8 * a8)) + 4 * (lane & 1);
+      }
+  }
   auto read_vt = [&](const uint16_t* vt, int key0, int db) -> bf16x8 {
     // contraction slots (hh, jj): jj < 4 -> keys key0 + 4*hh + jj, jj >= 4 -> keys key0 + 8 + 4*hh + jj - 4
-    const uint16_t* p0 = vt + key0 * kVtStride + 32 * db + vt_lane_off;
-    const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p0));
-    const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p0 + 8 * kVtStride));
+    const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vt + key0 * kRowElems + voff[db][0]));
+    const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vt + key0 * kRowElems + voff[db][1]));
     u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
     u32x4 w = {l2.x, l2.y, h2.x, h2.y};
     return __builtin_bit_cast(bf16x8, w);
@@ -218,13 +240,13 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     for (int pre = 0; pre < 2; ++pre)
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb)
-        ka[pre][nb] = *reinterpret_cast<const bf16x8*>(ks + (32 * nb + m_) * kKsStride + 16 * pre + 8 * hh);
+        ka[pre][nb] = *reinterpret_cast<const bf16x8*>(ks + 32 * nb * kRowElems + koff[pre]);
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       if (kk + 2 < 8) {
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb)
-          ka[(kk + 2) % 3][nb] = *reinterpret_cast<const bf16x8*>(ks + (32 * nb + m_) * kKsStride + 16 * (kk + 2) + 8 * hh);
+          ka[(kk + 2) % 3][nb] = *reinterpret_cast<const bf16x8*>(ks + 32 * nb * kRowElems + koff[kk + 2]);
       }
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb)
@@ -305,8 +327,8 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     }
   };
 
+  load_index(0);
   load_tile(0);
-  store_tile(0);
   __syncthreads();
 
   // Every wavefront runs the same sequence of barriers, one per key tile.  A wavefront whose
@@ -326,7 +348,6 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
       l_run = prev + mass;
       m_ref = m_use;
     }
-    if (it + 1 < ntiles) store_tile(it + 1);
     __syncthreads();
   }
   // ---- prefix tiles in KV_perm order (Pass-2) with the early-stop rule: the query tile
@@ -358,7 +379,6 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     qk(it & 1);
     softmax(std::false_type{}, it);
     publish(it);
-    if (it + 1 < ntiles) store_tile(it + 1);
     __syncthreads();
     ++it;
     for (; it < ntiles; ++it) {
@@ -388,7 +408,6 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
       ++committed;
       softmax(std::false_type{}, it);
       publish(it);
-      if (it + 1 < ntiles) store_tile(it + 1);
       __syncthreads();
     }
     if (pending) {                                     // the last prefix tile: its vote is visible now
@@ -416,7 +435,6 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
       }
       if (it + 1 < ntiles) load_tile(it + 1);
       if (lane == 0) vote_flags(it)[wave] = 0;
-      if (it + 1 < ntiles) store_tile(it + 1);
       __syncthreads();
     }
   }
