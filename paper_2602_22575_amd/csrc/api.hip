@@ -29,6 +29,7 @@ bool fill_strides(const int64_t in[3], int64_t out[3], int heads, int L, int D) 
   }
   for (int i = 0; i < 3; ++i) {
     if (in[i] < 0 || (in[i] % 8) != 0) return false;   // 16-byte aligned rows
+    if (i == 2 && in[i] > (1 << 24)) return false;     // row stride in bytes must fit 32 bits
     out[i] = in[i];
   }
   return out[2] >= D;

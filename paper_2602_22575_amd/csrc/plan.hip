@@ -55,7 +55,7 @@ constexpr int kSpanCap = 4096;     // elements one span_sort workgroup sorts in 
 constexpr int kSubBuckets = 2048;  // fine buckets of the in-LDS sort
 constexpr int kSubMax = 64;        // a fuller sub-bucket sends the span to the bitonic fallback
 constexpr int kChunk = 1024;       // key tokens per score workgroup
-constexpr int kSub = 64;           // key tokens per LDS tile of the score kernel
+constexpr int kSub = 64;           // key tokens per LDS tile of the score kernel (32 in the scatter pass)
 constexpr int kKStride = 136;      // bf16 elements per K row in LDS (272 B)
 constexpr int kBigGrid = 64;       // workgroups of the fallback sort
 
@@ -259,10 +259,14 @@ __global__ __launch_bounds__(256) void pool_sq_sort_kernel(PlanArgs a, Scratch s
 //                            so a lane sees one row only and its meta data are scalars
 template <int MODE>
 __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
+  // the scatter pass keeps a 32-bit cursor per (row, bucket) in LDS and pays for it with a
+  // smaller K tile
+  constexpr int kSubT = MODE == 2 ? 32 : kSub;
+  constexpr int kCntWords = MODE == 2 ? kNBMax : kNBMax / 2;   // LDS words per row of counters
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t* Kt = reinterpret_cast<uint16_t*>(smem);                          // [kSub][kKStride]
-  uint32_t* hist_all = reinterpret_cast<uint32_t*>(smem + kSub * kKStride * 2);  // [4][32][kNBMax/2]
-  float* spl_all = reinterpret_cast<float*>(hist_all + 4 * 32 * (kNBMax / 2));   // [4][32][kSplStride]
+  uint16_t* Kt = reinterpret_cast<uint16_t*>(smem);                          // [kSubT][kKStride]
+  uint32_t* hist_all = reinterpret_cast<uint32_t*>(smem + kSubT * kKStride * 2);  // [4][32][kCntWords]
+  float* spl_all = reinterpret_cast<float*>(hist_all + 4 * 32 * kCntWords);      // [4][32][kSplStride]
 
   const int G = a.H / a.Hkv;
   const int R = G * a.N;
@@ -304,7 +308,6 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
   const int64_t zh = (int64_t)z * a.H + g * G + rr / a.N;
   const int64_t row_id = zh * a.N + rr % a.N;
   const int64_t base = zh * kv_row_offset(a.N, a.S) + kv_row_offset(rr % a.N, a.S);
-  const int64_t cell = (row_id * sc.maxch + chunk) * kNBMax;
 
   // B fragments: 3 split terms x 8 contraction steps
   bf16x8 bq[3][8];
@@ -317,14 +320,18 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
         bq[t][kk] = *reinterpret_cast<const bf16x8*>(qs + t * kD + 16 * kk + 8 * hh);
   }
 
-  uint32_t* hist = hist_all + wave * 32 * (kNBMax / 2);   // two 16-bit counters per word
+  // MODE 1: two 16-bit counters per word; MODE 2: one cursor per word, preset to the cell's
+  // offset inside its row
+  uint32_t* hist = hist_all + wave * 32 * kCntWords;
   float* spl = spl_all + wave * 32 * kSplStride;           // this wavefront's rows' splitters
   if (MODE != 0) {
-    for (int i = lane; i < 32 * (kNBMax / 2); i += 64) hist[i] = 0;
+    if (MODE == 1)
+      for (int i = lane; i < 32 * kCntWords; i += 64) hist[i] = 0;
     for (int i = 0; i < 32; ++i) {
       const int r2 = min(32 * rb + i, R - 1);
       const int64_t rid2 = ((int64_t)z * a.H + g * G + r2 / a.N) * a.N + r2 % a.N;
       spl[i * kSplStride + lane] = sc.splitters[rid2 * kNBMax + lane];
+      if (MODE == 2) hist[i * kCntWords + lane] = sc.coffs[(rid2 * sc.maxch + chunk) * kNBMax + lane];
     }
   }
   const float* myspl = spl + m_ * kSplStride;
@@ -333,29 +340,29 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
   // K tile loader: thread (c, q) moves 16-byte chunk c of rows q, q+16, ...
   const uint16_t* Kh = a.K + z * a.ks[0] + g * a.ks[1];
   const int c = tid & 15, q = tid >> 4;
-  u32x4 kreg[kSub / 16];
+  u32x4 kreg[kSubT / 16];
   auto load_tile = [&](int t0) {
 #pragma unroll
-    for (int s = 0; s < kSub / 16; ++s) {
+    for (int s = 0; s < kSubT / 16; ++s) {
       const int t = min(t0 + q + 16 * s, a.L - 1);
       kreg[s] = *reinterpret_cast<const u32x4*>(Kh + (int64_t)t * a.ks[2] + 8 * c);
     }
   };
   auto store_tile = [&]() {
 #pragma unroll
-    for (int s = 0; s < kSub / 16; ++s)
+    for (int s = 0; s < kSubT / 16; ++s)
       *reinterpret_cast<u32x4*>(Kt + (q + 16 * s) * kKStride + 8 * c) = kreg[s];
   };
 
   load_tile(t_begin);
-  for (int t0 = t_begin; t0 < t_end; t0 += kSub) {
+  for (int t0 = t_begin; t0 < t_end; t0 += kSubT) {
     __syncthreads();                       // previous tile fully consumed
     store_tile();
     __syncthreads();
-    if (t0 + kSub < t_end) load_tile(t0 + kSub);
+    if (t0 + kSubT < t_end) load_tile(t0 + kSubT);
     if (t0 < lim_wave) {
 #pragma unroll 1
-      for (int sb = 0; sb < kSub / 32; ++sb) {
+      for (int sb = 0; sb < kSubT / 32; ++sb) {
         f32x16 acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
@@ -401,13 +408,10 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
 #pragma unroll
                 for (int step = kNBMax / 2; step > 0; step >>= 1)
                   bk += myspl[bk + step - 1] > sv ? step : 0;
-                const uint32_t inc = 1u << (16 * (bk & 1));
                 if (MODE == 1) {
-                  atomicAdd(&hist[m_ * (kNBMax / 2) + (bk >> 1)], inc);
+                  atomicAdd(&hist[m_ * kCntWords + (bk >> 1)], 1u << (16 * (bk & 1)));
                 } else {
-                  const uint32_t w = atomicAdd(&hist[m_ * (kNBMax / 2) + (bk >> 1)], inc);
-                  const uint32_t rank = (w >> (16 * (bk & 1))) & 0xffffu;
-                  const uint32_t pos = sc.coffs[cell + bk] + rank;
+                  const uint32_t pos = atomicAdd(&hist[m_ * kCntWords + bk], 1u);
                   if (pos < (uint32_t)lim) sc.pairs[base + pos] = sort_key(sv, (uint32_t)(t + e));
                   else sc.counters[2] = 1u;
                 }
@@ -428,7 +432,7 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
         const int64_t zh2 = (int64_t)z * a.H + g * G + r2 / a.N;
         const int64_t cell2 = ((zh2 * a.N + r2 % a.N) * sc.maxch + chunk) * kNBMax;
         if (lane < kNBMax / 2)
-          reinterpret_cast<uint32_t*>(sc.chist + cell2)[lane] = hist[i * (kNBMax / 2) + lane];
+          reinterpret_cast<uint32_t*>(sc.chist + cell2)[lane] = hist[i * kCntWords + lane];
       }
     }
   }
@@ -710,6 +714,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
     const int nchunks = (a.L + kChunk - 1) / kChunk;
     const dim3 grid((unsigned)((int64_t)a.Z * a.Hkv * RBG * nchunks));
     const size_t lds = (size_t)kSub * kKStride * 2 + 4 * 32 * (kNBMax / 2) * 4 + 4 * 32 * kSplStride * 4;
+    const size_t lds2 = (size_t)32 * kKStride * 2 + 4 * 32 * kNBMax * 4 + 4 * 32 * kSplStride * 4;
     static bool attr2_set = false;
     if (!attr2_set) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<0>),
@@ -717,7 +722,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
       if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<1>),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<2>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
       if (e != hipSuccess) return e;
       attr2_set = true;
     }
@@ -729,7 +734,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
     }
     hipLaunchKernelGGL(score_kernel<1>, grid, dim3(256), lds, stream, a, sc);
     hipLaunchKernelGGL(scan_kernel, dim3((unsigned)rows), dim3(4 * kNBMax), 0, stream, a, sc);
-    hipLaunchKernelGGL(score_kernel<2>, grid, dim3(256), lds, stream, a, sc);
+    hipLaunchKernelGGL(score_kernel<2>, grid, dim3(256), lds2, stream, a, sc);
     const int64_t sort_grid = sc.max_spans < 8192 ? sc.max_spans : 8192;
     hipLaunchKernelGGL(span_sort_kernel, dim3((unsigned)sort_grid), dim3(kSortThreads), 0, stream, a, sc);
     hipLaunchKernelGGL(big_sort_kernel, dim3(kBigGrid), dim3(256), 0, stream, a, sc);
