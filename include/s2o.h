@@ -55,8 +55,8 @@ typedef struct s2o_params {
   int32_t kv_heads;      /* Hkv, H % Hkv == 0                                              */
   int32_t seq_len;       /* L, L % seg_len == 0                                            */
   int32_t head_dim;      /* D, only 128                                                    */
-  int32_t seg_len;       /* S (paper default 2048), multiple of 64, 64 <= S <= 8192        */
-  int32_t block_m;       /* B_M: query tile rows, only 64                                  */
+  int32_t seg_len;       /* S (paper default 2048), multiple of B_M, S <= 8192             */
+  int32_t block_m;       /* B_M: query tile rows, 64 or 128                                */
   int32_t block_n;       /* B_N: key tile tokens, only 64                                  */
   int32_t use_q_perm;    /* 1: gather queries by Q_perm (Alg. 3); 0: original order (Alg. 4) */
   int32_t stop_mode;     /* 0: a triggering tile is discarded (Alg. 3/4 as printed);

@@ -46,8 +46,8 @@ int check_params(const s2o_params* p, Shape* s) {
   if (p->stop_mode != 0 && p->stop_mode != 1) return S2O_EINVAL;
   if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) return S2O_EINVAL;
   if (p->head_dim != 128) return S2O_EUNSUPPORTED;
-  if (p->block_m != 64 || p->block_n != 64) return S2O_EUNSUPPORTED;
-  if (p->seg_len % 64 != 0 || p->seg_len > 8192) return S2O_EUNSUPPORTED;
+  if ((p->block_m != 64 && p->block_m != 128) || p->block_n != 64) return S2O_EUNSUPPORTED;
+  if (p->seg_len % p->block_m != 0 || p->seg_len > 8192) return S2O_EUNSUPPORTED;
   if ((int64_t)p->batch * p->q_heads * (p->seq_len / p->seg_len) > (1 << 24)) return S2O_EUNSUPPORTED;
   s->Z = p->batch; s->H = p->q_heads; s->Hkv = p->kv_heads; s->L = p->seq_len;
   s->D = p->head_dim; s->S = p->seg_len; s->N = p->seq_len / p->seg_len;
@@ -70,7 +70,7 @@ const char* s2o_strerror(int code) {
   switch (code) {
     case S2O_OK: return "ok";
     case S2O_EINVAL: return "invalid argument";
-    case S2O_EUNSUPPORTED: return "unsupported configuration (need D=128, 64x64 tiles, S%64==0, S<=8192)";
+    case S2O_EUNSUPPORTED: return "unsupported configuration (need D=128, B_M in {64,128}, B_N=64, S%B_M==0, S<=8192)";
     case S2O_ESCRATCH: return "scratch buffer missing, misaligned or too small";
     case S2O_EHIP: return "HIP runtime error (see s2o_last_hip_error)";
     default: return "unknown error code";
@@ -153,6 +153,7 @@ int s2o_attention(const void* Q, const void* K, const void* V, const s2o_params*
   a.O = (uint16_t*)O;
   a.q_perm = q_perm; a.kv_perm = kv_perm; a.computed = computed; a.skipped = skipped;
   a.Z = s.Z; a.H = s.H; a.Hkv = s.Hkv; a.L = s.L; a.S = s.S; a.N = s.N;
+  a.BM = params->block_m;
   a.use_q_perm = params->use_q_perm; a.stop_mode = params->stop_mode;
   a.tau = tau;
   const float scale = params->softmax_scale > 0.f ? params->softmax_scale : 1.0f / sqrtf((float)s.D);

@@ -45,9 +45,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kD = 128;          // head dim
 constexpr int kBN = 64;          // key tile
-constexpr int kBM = 64;          // query tile (two wavefronts)
-constexpr int kTilesPerWg = 4;   // query tiles per workgroup
-constexpr int kWaves = 2 * kTilesPerWg;
+constexpr int kRowsPerWave = 32; // query rows of one wavefront
+constexpr int kWaves = 8;        // a query tile of B_M rows is B_M/32 wavefronts: 4 tiles of 64
+                                 // rows or 2 tiles of 128 rows per workgroup
 constexpr int kThreads = 64 * kWaves;
 constexpr int kRowElems = kD;    // K and V rows sit unpadded in LDS (256 B); the sixteen 16-byte
                                  // chunks of row r are stored at slot (chunk ^ swz(r)) instead
@@ -76,8 +76,11 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m_ = lane & 31, hh = lane >> 5;
   const int G = a.H / a.Hkv;
-  const int TJ = a.S / kBM;                              // query tiles per segment
-  const int JG = (TJ + kTilesPerWg - 1) / kTilesPerWg;   // workgroups per (z,h,n)
+  const int BM = a.BM;                                   // query tile rows: 64 or 128
+  const int wpt = BM / kRowsPerWave;                     // wavefronts per query tile
+  const int tpw = kWaves / wpt;                          // query tiles per workgroup
+  const int TJ = a.S / BM;                               // query tiles per segment
+  const int JG = (TJ + tpw - 1) / tpw;                   // workgroups per (z,h,n)
 
   // ---- block -> (z, h, n, jg).  Longest prefixes first.  Consecutive block ids are dealt
   // round-robin to the 8 XCDs, each with its own L2: the JG workgroups of one (z, h, n) walk
@@ -115,17 +118,17 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   const int nS = n * a.S;
   const int nK = nS / kBN;                     // prefix tiles of this segment
 
-  // wavefront -> (query tile of the workgroup, 32-row half); the two halves of a tile are
-  // wavefronts w and w + 4
-  const int half = wave >> 2;
-  const int j = jg * kTilesPerWg + (wave & 3);  // this wavefront's permuted query tile
+  // wavefront -> (query tile of the workgroup, 32-row part); the parts of a tile are
+  // wavefronts tile, tile + tpw, ...
+  const int tile_l = wave % tpw, part = wave / tpw;
+  const int j = jg * tpw + tile_l;              // this wavefront's permuted query tile
   bool active = j < TJ;
 
   // ---- the query row of this lane and its Q fragments
   int qoff;
   bf16x8 qf[8];
   {
-    const int r = min(j, TJ - 1) * kBM + 32 * half + m_;
+    const int r = min(j, TJ - 1) * BM + kRowsPerWave * part + m_;
     qoff = a.use_q_perm ? a.q_perm[(zh * a.N + n) * a.S + r] : r;
     qoff = min(max(qoff, 0), a.S - 1);
     const uint16_t* qrow = Qh + (int64_t)(nS + qoff) * a.qs[2];
@@ -386,7 +389,9 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
       int any = 0;
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) any |= vf[w];
-      const bool stop = (vf[wave & 3] | vf[4 + (wave & 3)]) == 0;
+      int votes = 0;
+      for (int p2 = 0; p2 < wpt; ++p2) votes |= vf[tile_l + tpw * p2];
+      const bool stop = votes == 0;
       if (stop && a.stop_mode == 0) {                  // the triggering tile is dropped
         l_run = l_save; m_ref = m_save;
         pending = false;
@@ -412,7 +417,9 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     }
     if (pending) {                                     // the last prefix tile: its vote is visible now
       const int* vf = vote_flags(ntiles - 1);
-      const bool stop = (vf[wave & 3] | vf[4 + (wave & 3)]) == 0;
+      int votes = 0;
+      for (int p2 = 0; p2 < wpt; ++p2) votes |= vf[tile_l + tpw * p2];
+      const bool stop = votes == 0;
       if (stop && a.stop_mode == 0) {
         l_run = l_save; m_ref = m_save;
       } else {
@@ -452,8 +459,8 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
         w.y = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
         *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * i4 + 4 * hh) = w;
       }
-    if (lane == 0 && half == 0) {
-      const int64_t ci = zh * (a.L / kBM) + (int64_t)n * TJ + j;
+    if (lane == 0 && part == 0) {
+      const int64_t ci = zh * (a.L / BM) + (int64_t)n * TJ + j;
       if (a.computed) a.computed[ci] = committed;
       if (a.skipped) a.skipped[ci] = nK - issued;
     }
@@ -468,8 +475,9 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int TJ = a.S / kBM;
-  const int JG = (TJ + kTilesPerWg - 1) / kTilesPerWg;
+  const int TJ = a.S / a.BM;
+  const int tpw = kWaves / (a.BM / kRowsPerWave);
+  const int JG = (TJ + tpw - 1) / tpw;
   const int64_t blocks = (int64_t)a.Z * a.H * a.N * JG;
   if (blocks <= 0 || blocks > 0x7fffffff) return hipErrorInvalidValue;
   hipLaunchKernelGGL(s2o_attention_kernel, dim3((unsigned)blocks), dim3(kThreads), kAttnLds, stream, a);

@@ -18,6 +18,7 @@ struct AttnArgs {
   int32_t* computed;
   int32_t* skipped;
   int Z, H, Hkv, L, S, N;
+  int BM;  // query tile rows (64 or 128); the key tile is 64 tokens
   int use_q_perm, stop_mode;
   float tau;
   float scale_log2e;  // softmax_scale * log2(e): logits are kept in base-2 units

@@ -48,7 +48,9 @@ def test_size_queries():
     (dict(H=6, Hkv=4), b.S2O_EINVAL),             # H % Hkv != 0
     (dict(Z=0), b.S2O_EINVAL),
     (dict(D=64), b.S2O_EUNSUPPORTED),
-    (dict(BM=128), b.S2O_EUNSUPPORTED),
+    (dict(BM=32), b.S2O_EUNSUPPORTED),
+    (dict(BM=128, S=192, L=768), b.S2O_EUNSUPPORTED),   # S % B_M != 0
+    (dict(BN=128), b.S2O_EUNSUPPORTED),
     (dict(S=96, L=960), b.S2O_EUNSUPPORTED),      # S % 64 != 0
     (dict(S=16384, L=32768), b.S2O_EUNSUPPORTED),
     (dict(stop_mode=2), b.S2O_EINVAL),

@@ -103,6 +103,29 @@ def test_tiny_without_query_permutation(tiny):
     assert np.abs(parity.to_f64(Ob) - fused).max() <= parity.O_MAX_ABS
 
 
+def test_tiny_128_row_query_tiles(tiny):
+    """B_M = 128 (query tile = four wavefronts voting together), B_N = 64."""
+    w0, (Qb, Kb, Vb), (Qd, Kd, Vd) = tiny
+    w = inputs.workload("tiny", BM=128)
+    plan, pg = gu.gpu_plan(w, Qd, Kd)
+    Q, K, V = (parity.to_f64(x) for x in (Qb, Kb, Vb))
+    for stop_mode in (0, 1):
+        gains = {(0, 0): orc.gain_profile(Q, K, V, pg["q_perm"], pg["kv_perm"], w.S, w.BM, w.BN, stop_mode=stop_mode)}
+        for tau in (0.0, 0.03, 0.1):
+            if tau > 0:
+                tau = parity.pick_tau(gains, tau)
+            _say(f"case: tiny 128x64 tiles tau={tau} stop_mode={stop_mode}")
+            Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, stop_mode)
+            assert c.shape[-1] == w.L // 128
+            st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, stop_mode, Ob, c, s,
+                                        gains=gains)
+            gains = st.pop("gains")
+            _say("  ", st, "density", orc.density(s, w.L, w.S, w.BM, w.BN))
+            assert st["ambiguous"] == 0
+            if tau > 0:
+                assert (s > 0).any()
+
+
 def test_determinism(tiny):
     w, (Qb, Kb, Vb), (Qd, Kd, Vd) = tiny
     a_plan, a = gu.gpu_plan(w, Qd, Kd)
@@ -188,12 +211,12 @@ def test_llama8k(gpu):
                 assert err.max() <= parity.O_MAX_ABS
 
 
-def _sampled_case(name, plan_heads, attn_samples, taus, stop_mode=0):
+def _sampled_case(name, plan_heads, attn_samples, taus, stop_mode=0, **overrides):
     """Full-size workload in the launch configuration bench.py times (all heads, whole
     sequence on the GPU); the oracle checks the plan on a few heads and the attention on a
     few (head, segment) pairs it can compute one by one."""
-    w = inputs.workload(name)
-    _say(f"case: {name} generate L={w.L}")
+    w = inputs.workload(name, **overrides)
+    _say(f"case: {name} {overrides} generate L={w.L}")
     Qb, Kb, Vb = inputs.make_qkv(w)
     Qd, Kd, Vd = (gu.to_dev(x) for x in (Qb, Kb, Vb))
     _say(f"case: {name} plan on the GPU")
@@ -232,3 +255,10 @@ def test_llama128k_sampled(gpu):
     (head, segment) pairs, at the threshold bench.py times and with skipping disabled on
     one short segment."""
     _sampled_case("llama128k", plan_heads=[3, 20], attn_samples=[(3, [1, 21]), (20, [42])], taus=(5e-3,))
+
+
+def test_mixed128k_sampled(gpu):
+    """128K with half the KV groups unstructured (stopping rarely fires) and half strongly
+    structured, for both query tile shapes (64x64 and 128x64)."""
+    _sampled_case("mixed128k", plan_heads=[2, 29], attn_samples=[(2, [3]), (29, [40])], taus=(5e-3,))
+    _sampled_case("mixed128k", plan_heads=[], attn_samples=[(2, [3]), (29, [40])], taus=(5e-3,), BM=128)
