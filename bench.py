@@ -49,6 +49,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama128k")
     ap.add_argument("--tau", type=float, default=5e-3)
+    ap.add_argument("--block-m", type=int, default=None, help="query tile rows (64 or 128); default: the workload's")
     ap.add_argument("--sweep", action="store_true", help="also time every tau of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mse", action="store_true")
@@ -67,7 +68,7 @@ def main():
         sys.exit(3)
     s2o.load_library()
     dev = torch.device("cuda:0")
-    w = inputs.workload(args.workload)
+    w = inputs.workload(args.workload) if args.block_m is None else inputs.workload(args.workload, BM=args.block_m)
     t0 = time.time()
     Qb, Kb, Vb = inputs.make_qkv(w)
     t_gen = time.time() - t0
@@ -175,8 +176,8 @@ def cpu_baseline(w, Qb, Kb, Vb, plan, tau, issued_tiles_gpu):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    heads = [0, w.H - 1] if w.H > 1 else [0]
-    segs = sorted({min(1, w.N - 1), w.N // 3}) if w.N > 2 else list(range(w.N))
+    heads = sorted({0, w.H // 6, (2 * w.H) // 5, (4 * w.H) // 7, (5 * w.H) // 6, w.H - 1})
+    segs = sorted({min(1, w.N - 1), w.N // 8, w.N // 4, w.N // 2, (3 * w.N) // 4, w.N - 1})
     G = w.G
     qp = plan.q_perm.cpu().numpy()
     kp = plan.kv_perm.cpu().numpy()
