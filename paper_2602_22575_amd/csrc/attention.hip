@@ -168,13 +168,17 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     for (int gi = 0; gi < 4; ++gi)
       tokn[gi] = it < nloc ? nS + it * kBN + 16 * (wave & 3) + 4 * gi + (lane >> 4) : ld[gi];
   };
+  const uint32_t stride_bytes = (uint32_t)(src_stride * 2);
+  const char* gbase[4];                 // per group: head base + this lane's (swizzled) chunk
+#pragma unroll
+  for (int gi = 0; gi < 4; ++gi)
+    gbase[gi] = reinterpret_cast<const char*>(src) + 16 * ((lane & 15) ^ swz(16 * (wave & 3) + 4 * gi + (lane >> 4)));
   auto load_tile = [&](int it) {       // K tiles alternate between 2 buffers, V tiles between 3
     uint16_t* dst = loads_v ? Vt + (it % 3) * kVtElems : Ks + (it & 1) * kKsElems;
 #pragma unroll
     for (int gi = 0; gi < 4; ++gi) {
-      const int row = 16 * (wave & 3) + 4 * gi + (lane >> 4);
-      const int tok = min(max(tokn[gi], 0), a.L - 1);
-      const uint16_t* gp = src + (int64_t)tok * src_stride + 8 * ((lane & 15) ^ swz(row));
+      const uint32_t tok = (uint32_t)min(max(tokn[gi], 0), a.L - 1);
+      const char* gp = gbase[gi] + (uint64_t)tok * stride_bytes;   // one 64-bit multiply-add
       __builtin_amdgcn_global_load_lds((const gvoid*)gp, (lvoid*)(dst + (16 * (wave & 3) + 4 * gi) * kRowElems),
                                        16, 0, 0);
     }
