@@ -53,6 +53,8 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="also time every tau of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mse", action="store_true")
+    ap.add_argument("--fused", action="store_true",
+                    help="one attention launch (no state buffers) instead of Alg. 2 and Alg. 3 separately")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); "
@@ -80,10 +82,14 @@ def main():
     O = torch.empty((w.Z, w.H, w.L, w.D), dtype=torch.bfloat16, device=dev)
     comp = torch.empty((w.Z, w.H, w.L // w.BM), dtype=torch.int32, device=dev)
     skip = torch.empty_like(comp)
+    # state buffers of the two-launch form (Alg. 2 then Alg. 3); --fused runs both in one launch
+    attn_scratch = None if args.fused else torch.empty(s2o.s2o_attention_sizes(params)["scratch"],
+                                                       dtype=torch.uint8, device=dev)
+    akw = dict(scratch=attn_scratch, two_pass=not args.fused)
 
     def step(tau):
         plan = s2o.s2o_plan(Qd, Kd, params, want_scores=False, scratch=scratch)
-        s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau, O=O, computed=comp, skipped=skip)
+        s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau, O=O, computed=comp, skipped=skip, **akw)
         return plan
 
     def timed(fn, iters):
@@ -108,7 +114,7 @@ def main():
     plan_ms = float(np.mean(timed(lambda: s2o.s2o_plan(Qd, Kd, params, want_scores=False, scratch=scratch),
                                   max(args.steps, 3))))
     attn_fn = lambda tau: s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau, O=O,
-                                            computed=comp, skipped=skip)
+                                            computed=comp, skipped=skip, **akw)
     attn_ms = float(np.mean(timed(lambda: attn_fn(args.tau), max(args.steps, 3))))
     c, s = comp.cpu().numpy(), skip.cpu().numpy()
     flops, trig = tile_flops(w, c, s)
@@ -121,7 +127,7 @@ def main():
         O_tau = O.float()
         Od = torch.empty_like(O)
         dense_ms = float(np.mean(timed(lambda: s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm,
-                                                                 0.0, O=Od), 2)))
+                                                                 0.0, O=Od, **akw), 2)))
         ref = Od.float()
         per_head = ((O_tau - ref) ** 2).mean(dim=(0, 2, 3))
         extra["mse_vs_dense"] = float(per_head.mean())

@@ -100,7 +100,8 @@ int s2o_plan_sizes(const s2o_params* params, size_t* q_perm_bytes, size_t* kv_pe
 int s2o_plan(const void* Q, const void* K, const s2o_params* params, const s2o_plan_out* out,
              void* scratch, size_t scratch_bytes, void* stream);
 
-/* Byte sizes of one counts array ([Z,H,L/B_M] int32) and of the attention scratch. */
+/* Byte sizes of one counts array ([Z,H,L/B_M] int32) and of the optional attention scratch
+ * (the per-row state buffers of the two-pass form, fp32 [Z,H,L,D+2]). */
 int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* scratch_bytes);
 
 /* Step 2 (Alg. 2 + Alg. 3, or Alg. 4 when use_q_perm == 0).
@@ -116,7 +117,13 @@ int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* 
  *   computed [Z,H,L/B_M] prefix tiles folded into the output of permuted query tile
  *            n*(S/B_M)+j; skipped: prefix tiles never loaded.  n*S/B_N - computed - skipped
  *            is 1 when a triggering tile was loaded and discarded (stop_mode 0), else 0.
- *            Either may be NULL. */
+ *            Either may be NULL.
+ *   scratch  NULL: one fused launch (the own-segment window and the prefix walk share
+ *            registers).  Otherwise a device buffer, 256-byte aligned, of at least the size
+ *            s2o_attention_sizes reports: the two passes of the paper are launched
+ *            separately (Alg. 2 in original query order, its state kept in `scratch`, then
+ *            Alg. 3), which computes only the causal own-segment tiles.  Both forms give the
+ *            same result up to rounding order.  Ignored if use_q_perm == 0 and NULL. */
 int s2o_attention(const void* Q, const void* K, const void* V, const s2o_params* params,
                   const int32_t* q_perm, const int32_t* kv_perm, float tau, void* O,
                   int32_t* computed, int32_t* skipped, void* scratch, size_t scratch_bytes,

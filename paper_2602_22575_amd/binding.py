@@ -167,8 +167,10 @@ def s2o_plan(Q, K, params: S2OParams, want_scores: bool = True, scratch=None, st
 
 
 def s2o_attention(Q, K, V, params: S2OParams, q_perm, kv_perm, tau: float, O=None,
-                  computed=None, skipped=None, stream=None):
-    """Step 2.  Returns (O [Z,H,L,D] bf16, computed, skipped int32 [Z,H,L/B_M])."""
+                  computed=None, skipped=None, stream=None, scratch=None, two_pass=True):
+    """Step 2.  Returns (O [Z,H,L,D] bf16, computed, skipped int32 [Z,H,L/B_M]).
+    two_pass: launch Alg. 2 and Alg. 3 separately (needs `scratch`, allocated here if not
+    given); False: one fused launch."""
     import torch
     lib = load_library()
     sz = s2o_attention_sizes(params)
@@ -180,9 +182,12 @@ def s2o_attention(Q, K, V, params: S2OParams, q_perm, kv_perm, tau: float, O=Non
         computed = torch.empty((Z, H, L // params.block_m), dtype=torch.int32, device=dev)
     if skipped is None:
         skipped = torch.empty((Z, H, L // params.block_m), dtype=torch.int32, device=dev)
-    scratch = torch.empty(max(sz["scratch"], 256), dtype=torch.uint8, device=dev)
+    if two_pass and scratch is None:
+        scratch = torch.empty(sz["scratch"], dtype=torch.uint8, device=dev)
+    if not two_pass:
+        scratch = None
     _check(lib.s2o_attention(Q.data_ptr(), K.data_ptr(), V.data_ptr(), C.byref(params),
                              _ptr(q_perm), _ptr(kv_perm), float(tau), O.data_ptr(),
-                             computed.data_ptr(), skipped.data_ptr(), scratch.data_ptr(),
-                             scratch.numel(), _stream_handle(stream)))
+                             computed.data_ptr(), skipped.data_ptr(), _ptr(scratch),
+                             0 if scratch is None else scratch.numel(), _stream_handle(stream)))
     return O, computed, skipped

@@ -127,7 +127,7 @@ int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* 
   const int rc = check_params(params, &s);
   if (rc != S2O_OK) return rc;
   if (counts_bytes) *counts_bytes = (size_t)s.Z * s.H * (s.L / params->block_m) * 4;
-  if (scratch_bytes) *scratch_bytes = 0;   // Pass-1 state stays in registers
+  if (scratch_bytes) *scratch_bytes = s2o::attention_state_bytes(s.Z, s.H, s.L);
   return S2O_OK;
 }
 
@@ -135,7 +135,6 @@ int s2o_attention(const void* Q, const void* K, const void* V, const s2o_params*
                   const int32_t* q_perm, const int32_t* kv_perm, float tau, void* O,
                   int32_t* computed, int32_t* skipped, void* scratch, size_t scratch_bytes,
                   void* stream) {
-  (void)scratch; (void)scratch_bytes;
   Shape s;
   const int rc = check_params(params, &s);
   if (rc != S2O_OK) return rc;
@@ -146,6 +145,8 @@ int s2o_attention(const void* Q, const void* K, const void* V, const s2o_params*
   if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(O, 16) ||
       misaligned(kv_perm, 16))
     return S2O_EINVAL;
+  if (scratch && (misaligned(scratch, 256) || scratch_bytes < s2o::attention_state_bytes(s.Z, s.H, s.L)))
+    return S2O_ESCRATCH;
 
   s2o::AttnArgs a;
   memset(&a, 0, sizeof(a));
@@ -154,6 +155,12 @@ int s2o_attention(const void* Q, const void* K, const void* V, const s2o_params*
   a.q_perm = q_perm; a.kv_perm = kv_perm; a.computed = computed; a.skipped = skipped;
   a.Z = s.Z; a.H = s.H; a.Hkv = s.Hkv; a.L = s.L; a.S = s.S; a.N = s.N;
   a.BM = params->block_m;
+  if (scratch) {
+    const size_t rows = (size_t)s.Z * s.H * s.L;
+    a.st_acc = (float*)scratch;
+    a.st_l = a.st_acc + rows * s.D;
+    a.st_m = a.st_l + rows;
+  }
   a.use_q_perm = params->use_q_perm; a.stop_mode = params->stop_mode;
   a.tau = tau;
   const float scale = params->softmax_scale > 0.f ? params->softmax_scale : 1.0f / sqrtf((float)s.D);

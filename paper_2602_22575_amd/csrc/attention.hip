@@ -42,6 +42,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kD = 128;          // head dim
 constexpr int kBN = 64;          // key tile
@@ -67,6 +68,14 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, t);
 }
 
+// PASS 0: everything in one launch (own-segment window, then the prefix walk).
+// PASS 1: Alg. 2 alone -- queries in original order, exactly the causal own-segment tiles,
+//         leaves (acc, l, m) per row in the state buffers (A, Lbuf, Mbuf of the paper).
+// PASS 2: Alg. 3 alone -- gathers the queries and their states by Q_perm and walks the prefix.
+// Two launches cost a round trip of the fp32 state through HBM but halve the own-segment
+// work: a permuted query tile needs every own-segment key tile (with a per-element mask),
+// a tile in original order only those up to its diagonal.
+template <int PASS>
 __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
@@ -116,7 +125,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   const int64_t zh = (int64_t)z * a.H + h;
   const int32_t* kvrow = a.kv_perm + zh * kv_row_offset(a.N, a.S) + kv_row_offset(n, a.S);
   const int nS = n * a.S;
-  const int nK = nS / kBN;                     // prefix tiles of this segment
+  const int nK = PASS == 1 ? 0 : nS / kBN;     // prefix tiles this launch walks
 
   // wavefront -> (query tile of the workgroup, 32-row part); the parts of a tile are
   // wavefronts tile, tile + tpw, ...
@@ -129,7 +138,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   bf16x8 qf[8];
   {
     const int r = min(j, TJ - 1) * BM + kRowsPerWave * part + m_;
-    qoff = a.use_q_perm ? a.q_perm[(zh * a.N + n) * a.S + r] : r;
+    qoff = (a.use_q_perm && PASS != 1) ? a.q_perm[(zh * a.N + n) * a.S + r] : r;
     qoff = min(max(qoff, 0), a.S - 1);
     const uint16_t* qrow = Qh + (int64_t)(nS + qoff) * a.qs[2];
 #pragma unroll
@@ -142,7 +151,8 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   int wg_pmax = -1;
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) wg_pmax = max(wg_pmax, sflag[w]);
-  const int nloc = wg_pmax / kBN + 1;          // own-segment key tiles this workgroup needs
+  // own-segment key tiles this workgroup needs (none in the second pass of two)
+  const int nloc = PASS == 2 ? 0 : wg_pmax / kBN + 1;
   const int ntiles = nloc + nK;
 
   // ---- loader: wavefronts 0-3 move K, 4-7 move V, 4 groups of 4 rows each per tile; in a
@@ -228,6 +238,20 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
   int committed = 0, issued = 0;
   const float c2 = a.scale_log2e;
+  // state buffers: row (z, h, l) -> acc [128] fp32 in the accumulator's register order, l, m
+  const int64_t st_row = zh * a.L + nS + qoff;
+  if (PASS == 2 && active) {
+    const float* sp = a.st_acc + st_row * kD + 64 * hh;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(sp + 16 * db + 4 * i4);
+        o[db][4 * i4] = v[0]; o[db][4 * i4 + 1] = v[1]; o[db][4 * i4 + 2] = v[2]; o[db][4 * i4 + 3] = v[3];
+      }
+    l_run = a.st_l[st_row];
+    m_ref = a.st_m[st_row];
+  }
 
   // values a tile's score step hands to its PV step
   f32x16 s[2];
@@ -347,7 +371,10 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     if (it + 1 < ntiles) load_tile(it + 1);
     if (it * kBN <= wave_pmax) {       // wave_pmax = -1 for a wavefront without a query tile
       qk(it & 1);
-      softmax(std::true_type{}, it);
+      // the causal mask only matters if some row of the wavefront ends inside this tile
+      // (never skipped for permuted rows, whose positions are scattered)
+      if (PASS == 1 && it * kBN + kBN - 1 <= wave_pmax - (kRowsPerWave - 1)) softmax(std::false_type{}, it);
+      else softmax(std::true_type{}, it);
       bf16x8 pb[4];
       pack_p(pb);
       rescale(alpha, grow);
@@ -451,32 +478,53 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   }
 
   if (j < TJ) {
-    // normalise and scatter to the original row: lane holds dims 32*db + 8*(i/4) + 4*hh + i%4
-    const float inv = 1.0f / l_run;
-    uint16_t* orow = Oh + (int64_t)(nS + qoff) * a.os[2];
+    if (PASS == 1) {
+      // leave the un-normalised state for the second pass
+      float* sp = a.st_acc + st_row * kD + 64 * hh;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+      for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        u32x2 w;
-        w.x = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
-        w.y = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
-        *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * i4 + 4 * hh) = w;
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const f32x4 v = {o[db][4 * i4], o[db][4 * i4 + 1], o[db][4 * i4 + 2], o[db][4 * i4 + 3]};
+          *reinterpret_cast<f32x4*>(sp + 16 * db + 4 * i4) = v;
+        }
+      if (hh == 0) { a.st_l[st_row] = l_run; a.st_m[st_row] = m_ref; }
+    } else {
+      // normalise and scatter to the original row: lane holds dims 32*db + 8*(i/4) + 4*hh + i%4
+      const float inv = 1.0f / l_run;
+      uint16_t* orow = Oh + (int64_t)(nS + qoff) * a.os[2];
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          u32x2 w;
+          w.x = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
+          w.y = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
+          *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * i4 + 4 * hh) = w;
+        }
+      if (lane == 0 && part == 0) {
+        const int64_t ci = zh * (a.L / BM) + (int64_t)n * TJ + j;
+        if (a.computed) a.computed[ci] = committed;
+        if (a.skipped) a.skipped[ci] = nK - issued;
       }
-    if (lane == 0 && part == 0) {
-      const int64_t ci = zh * (a.L / BM) + (int64_t)n * TJ + j;
-      if (a.computed) a.computed[ci] = committed;
-      if (a.skipped) a.skipped[ci] = nK - issued;
     }
   }
+}
+
+size_t attention_state_bytes(int Z, int H, int L) {
+  return (size_t)Z * H * L * (kD + 2) * sizeof(float);
 }
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&s2o_attention_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds);
-    if (e != hipSuccess) return e;
+    const void* fns[3] = {reinterpret_cast<const void*>(&s2o_attention_kernel<0>),
+                          reinterpret_cast<const void*>(&s2o_attention_kernel<1>),
+                          reinterpret_cast<const void*>(&s2o_attention_kernel<2>)};
+    for (const void* f : fns) {
+      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds);
+      if (e != hipSuccess) return e;
+    }
     attr_set = true;
   }
   const int TJ = a.S / a.BM;
@@ -484,7 +532,13 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
   const int JG = (TJ + tpw - 1) / tpw;
   const int64_t blocks = (int64_t)a.Z * a.H * a.N * JG;
   if (blocks <= 0 || blocks > 0x7fffffff) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(s2o_attention_kernel, dim3((unsigned)blocks), dim3(kThreads), kAttnLds, stream, a);
+  const dim3 grid((unsigned)blocks), block(kThreads);
+  if (a.st_acc == nullptr) {
+    hipLaunchKernelGGL(s2o_attention_kernel<0>, grid, block, kAttnLds, stream, a);
+  } else {
+    hipLaunchKernelGGL(s2o_attention_kernel<1>, grid, block, kAttnLds, stream, a);
+    hipLaunchKernelGGL(s2o_attention_kernel<2>, grid, block, kAttnLds, stream, a);
+  }
   return hipGetLastError();
 }
 

@@ -17,6 +17,9 @@ struct AttnArgs {
   const int32_t* kv_perm;
   int32_t* computed;
   int32_t* skipped;
+  float* st_acc;  // two-pass state (NULL: one fused launch): [Z*H*L][128], then l and m [Z*H*L]
+  float* st_l;
+  float* st_m;
   int Z, H, Hkv, L, S, N;
   int BM;  // query tile rows (64 or 128); the key tile is 64 tokens
   int use_q_perm, stop_mode;
@@ -41,6 +44,7 @@ struct PlanArgs {
 };
 
 size_t plan_scratch_bytes(int Z, int H, int Hkv, int L, int S);
+size_t attention_state_bytes(int Z, int H, int L);
 hipError_t launch_plan(const PlanArgs& a, hipStream_t stream);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t stream);
 

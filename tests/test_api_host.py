@@ -40,7 +40,9 @@ def test_size_queries():
     assert sz["kv_perm"] == 32 * P * 4 and sz["s_k"] == sz["kv_perm"]
     assert sz["q_mean"] == 32 * N * 128 * 4 and sz["k_guide"] == 8 * 128 * 4
     assert sz["scratch"] >= 32 * P * 8 and sz["scratch"] % 256 == 0
-    assert b.s2o_attention_sizes(p)["counts"] == 32 * (131072 // 64) * 4
+    asz = b.s2o_attention_sizes(p)
+    assert asz["counts"] == 32 * (131072 // 64) * 4
+    assert asz["scratch"] == 32 * 131072 * (128 + 2) * 4      # fp32 acc, l, m per query row
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -91,6 +93,10 @@ def test_null_and_scratch_errors_come_before_any_hip_call(lib):
     assert lib.s2o_attention(*bad) == b.S2O_EINVAL
     bad = list(args); bad[6] = C.c_float(float("nan"))
     assert lib.s2o_attention(*bad) == b.S2O_EINVAL
+    bad = list(args); bad[10] = fake; bad[11] = 4096   # two-pass state buffer too small
+    assert lib.s2o_attention(*bad) == b.S2O_ESCRATCH
+    bad = list(args); bad[10] = C.c_void_p(0x10010); bad[11] = 1 << 40
+    assert lib.s2o_attention(*bad) == b.S2O_ESCRATCH
     p.struct_size = 8
     assert lib.s2o_attention(*args) == b.S2O_EINVAL
     assert lib.s2o_strerror(b.S2O_ESCRATCH).decode().startswith("scratch")

@@ -37,8 +37,9 @@ def test_tiny_plan_is_exact(tiny):
     assert np.array_equal(pg["kv_perm"], ref["kv_perm"])
 
 
+@pytest.mark.parametrize("two_pass", [True, False])
 @pytest.mark.parametrize("stop_mode", [0, 1])
-def test_tiny_attention(tiny, stop_mode):
+def test_tiny_attention(tiny, stop_mode, two_pass):
     w, (Qb, Kb, Vb), (Qd, Kd, Vd) = tiny
     plan, pg = gu.gpu_plan(w, Qd, Kd)
     Q, K, V = (parity.to_f64(x) for x in (Qb, Kb, Vb))
@@ -47,8 +48,8 @@ def test_tiny_attention(tiny, stop_mode):
     for tau in (0.0, -1.0, 0.02, 0.05, 0.2):
         if tau > 0:
             tau = parity.pick_tau(gains, tau)       # fixed by the oracle: no knife-edge decision
-        _say(f"case: tiny attention tau={tau} stop_mode={stop_mode}")
-        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, stop_mode)
+        _say(f"case: tiny attention tau={tau} stop_mode={stop_mode} two_pass={two_pass}")
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, stop_mode, two_pass=two_pass)
         st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, stop_mode, Ob, c, s,
                                     gains=gains)
         gains = st.pop("gains")
@@ -94,8 +95,10 @@ def test_tiny_without_query_permutation(tiny):
     plan, pg = gu.gpu_plan(w, Qd, Kd)
     for tau in (0.0, 0.05):
         _say(f"case: tiny use_q_perm=0 tau={tau}")
-        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, None, plan.kv_perm, tau, use_q_perm=0)
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, None, plan.kv_perm, tau, use_q_perm=0, two_pass=False)
         st = parity.check_attention(w, Qb, Kb, Vb, None, pg["kv_perm"], tau, 0, Ob, c, s, use_q_perm=False)
+        O2, c2, s2 = gu.gpu_attention(w, Qd, Kd, Vd, None, plan.kv_perm, tau, use_q_perm=0, two_pass=True)
+        parity.check_attention(w, Qb, Kb, Vb, None, pg["kv_perm"], tau, 0, O2, c2, s2, use_q_perm=False)
         st.pop("gains")
         _say("  ", st)
     Q, K, V = (parity.to_f64(x) for x in (Qb, Kb, Vb))
@@ -103,7 +106,8 @@ def test_tiny_without_query_permutation(tiny):
     assert np.abs(parity.to_f64(Ob) - fused).max() <= parity.O_MAX_ABS
 
 
-def test_tiny_128_row_query_tiles(tiny):
+@pytest.mark.parametrize("two_pass", [True, False])
+def test_tiny_128_row_query_tiles(tiny, two_pass):
     """B_M = 128 (query tile = four wavefronts voting together), B_N = 64."""
     w0, (Qb, Kb, Vb), (Qd, Kd, Vd) = tiny
     w = inputs.workload("tiny", BM=128)
@@ -114,8 +118,9 @@ def test_tiny_128_row_query_tiles(tiny):
         for tau in (0.0, 0.03, 0.1):
             if tau > 0:
                 tau = parity.pick_tau(gains, tau)
-            _say(f"case: tiny 128x64 tiles tau={tau} stop_mode={stop_mode}")
-            Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, stop_mode)
+            _say(f"case: tiny 128x64 tiles tau={tau} stop_mode={stop_mode} two_pass={two_pass}")
+            Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, stop_mode,
+                                        two_pass=two_pass)
             assert c.shape[-1] == w.L // 128
             st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, stop_mode, Ob, c, s,
                                         gains=gains)
@@ -150,10 +155,11 @@ def test_edge_shapes(gpu, L, S, H, Hkv):
     stats = parity.check_plan(w, Qb, Kb, pg)
     _say("  plan", stats)
     for tau in (0.0, 0.03):
-        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau)
-        st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, 0, Ob, c, s)
-        st.pop("gains")
-        _say("  attn", tau, st)
+        for two_pass in (True, False):
+            Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, two_pass=two_pass)
+            st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, 0, Ob, c, s)
+            st.pop("gains")
+            _say("  attn", tau, "two_pass" if two_pass else "fused", st)
 
 
 def test_degenerate_scores_take_the_fallback_sort(gpu):
