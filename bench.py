@@ -2,8 +2,9 @@
 """Benchmark of the S2O prefill-attention hot path on one MI355X.
 
 A step is one pass of the whole path over one synthetic batch that is already resident in
-HBM: s2o_plan (ranking: pooling, scores, both Argsorts) followed by s2o_attention (dense
-intra-segment window + ranked prefix walk with early stopping) at one threshold.  Prints
+HBM: s2o_plan (ranking: pooling, scores, both Argsorts), s2o_attention_local (dense causal
+window inside every segment; independent of the ranking, so it runs on a second stream beside
+it) and s2o_attention_prefix (ranked prefix walk with early stopping) at one threshold.  Prints
 ONE JSON line (see the keys below); `value` is the time of that whole step in ms/layer.
 """
 from __future__ import annotations
@@ -23,16 +24,56 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0
 
 
+def local_tiles(w):
+    """B_M x B_N score tiles of the own-segment causal windows, per head (diagonal tiles whole)."""
+    return w.N * sum(-(-((b + 1) * w.BM) // w.BN) for b in range(w.S // w.BM))
+
+
+def prefix_tiles(w):
+    """int array [L/B_M]: prefix tiles that exist for each query tile (n * S / B_N in segment n)."""
+    return np.repeat(np.arange(w.N) * (w.S // w.BN), w.S // w.BM)
+
+
+def density_of(w, skipped):
+    """Issued fraction of the causal score area per head: own-segment tiles plus every prefix
+    tile that was loaded (folded in or triggering)."""
+    causal = sum(-(-((b + 1) * w.BM) // w.BN) for b in range(w.L // w.BM))
+    issued = prefix_tiles(w)[None, None] - skipped
+    return (local_tiles(w) + issued.sum(axis=-1)) / causal
+
+
+def local_tile_flops(w):
+    """Algorithmic FLOPs of the own-segment pass alone (Alg. 2): QK^T and PV on its tiles."""
+    return float(local_tiles(w) * w.Z * w.H * 4 * w.BM * w.BN * w.D)
+
+
 def tile_flops(w, computed, skipped):
-    """Algorithmic FLOPs of one attention launch on computed blocks: Pass-1's causal
-    triangle of tiles + every folded-in prefix tile (QK^T and PV), + QK^T only for
-    triggering tiles that were discarded."""
-    from oracle.s2o_oracle import pass1_tiles, prefix_tiles  # bookkeeping helpers only
+    """Algorithmic FLOPs of the attention on computed blocks: the own-segment tiles + every
+    folded-in prefix tile (QK^T and PV), + QK^T only for triggering tiles that were discarded."""
     full = 4 * w.BM * w.BN * w.D
-    t1 = pass1_tiles(w.L, w.S, w.BM) * w.Z * w.H
-    total = prefix_tiles(w.L, w.S, w.BM, w.BN)[None, None]
-    trig = (total - computed - skipped).sum()
-    return float((t1 + computed.sum()) * full + trig * (full // 2)), int(trig)
+    trig = (prefix_tiles(w)[None, None] - computed - skipped).sum()
+    return float(local_tile_flops(w) + computed.sum() * full + trig * (full // 2)), int(trig)
+
+
+def recorded_traffic(workload, tau, block_m, kernel):
+    """HBM bytes per launch of `kernel` measured with rocprofv3 PMC counters (FETCH_SIZE and
+    WRITE_SIZE runs, scaled against a copy kernel of known size) for exactly this workload,
+    threshold and tiling, as recorded in the TRAFFIC lines of profiles/*.txt; None if no
+    such measurement is on file (counters cannot be read from inside this process)."""
+    import glob
+    want = {"workload": workload, "tau": repr(float(tau)), "block_m": str(block_m), "kernel": kernel}
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        for line in open(path):
+            if not line.startswith("TRAFFIC "):
+                continue
+            kv = dict(f.split("=", 1) for f in line.split()[1:])
+            try:
+                kv["tau"] = repr(float(kv.get("tau", "nan")))
+            except ValueError:
+                continue
+            if all(kv.get(k) == v for k, v in want.items()):
+                return float(kv["bytes"])
+    return None
 
 
 def plan_bytes(w):
@@ -53,6 +94,10 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="also time every tau of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mse", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain elementwise copy-like kernel (1 GiB read, 1 GiB written) so "
+                         "that HBM byte counters of a profiler run can be scaled against a known size")
+    ap.add_argument("--no-overlap", action="store_true", help="enqueue Alg. 2 on the same stream as the ranking")
     ap.add_argument("--fused", action="store_true",
                     help="one attention launch (no state buffers) instead of Alg. 2 and Alg. 3 separately")
     args = ap.parse_args()
@@ -79,17 +124,43 @@ def main():
     params = s2o.make_params(w.Z, w.H, w.Hkv, w.L, w.D, w.S, w.BM, w.BN)
     sizes = s2o.s2o_plan_sizes(params)
     scratch = torch.empty(sizes["scratch"], dtype=torch.uint8, device=dev)
+    P = w.S * w.N * (w.N - 1) // 2
+    maps = (torch.empty((w.Z, w.H, w.N, w.S), dtype=torch.int32, device=dev),
+            torch.empty((w.Z, w.H, max(P, 4)), dtype=torch.int32, device=dev))
     O = torch.empty((w.Z, w.H, w.L, w.D), dtype=torch.bfloat16, device=dev)
     comp = torch.empty((w.Z, w.H, w.L // w.BM), dtype=torch.int32, device=dev)
     skip = torch.empty_like(comp)
     # state buffers of the two-launch form (Alg. 2 then Alg. 3); --fused runs both in one launch
-    attn_scratch = None if args.fused else torch.empty(s2o.s2o_attention_sizes(params)["scratch"],
-                                                       dtype=torch.uint8, device=dev)
-    akw = dict(scratch=attn_scratch, two_pass=not args.fused)
+    state = None if args.fused else torch.empty(s2o.s2o_attention_sizes(params)["scratch"],
+                                                dtype=torch.uint8, device=dev)
+    main_stream = torch.cuda.current_stream()
+    side_stream = None if (args.fused or args.no_overlap) else torch.cuda.Stream()   # default priority
+
+    def do_plan():
+        return s2o.s2o_plan(Qd, Kd, params, want_scores=False, scratch=scratch, maps=maps)
 
     def step(tau):
-        plan = s2o.s2o_plan(Qd, Kd, params, want_scores=False, scratch=scratch)
-        s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau, O=O, computed=comp, skipped=skip, **akw)
+        """One pass of the hot path.  Alg. 2 needs neither map, so it is enqueued on a second
+        stream beside the ranking; Alg. 3 then waits for both."""
+        if args.fused:
+            plan = do_plan()
+            s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau, O=O, computed=comp,
+                              skipped=skip, two_pass=False)
+            return plan
+        if side_stream is None:
+            s2o.s2o_attention_local(Qd, Kd, Vd, params, scratch=state)
+            plan = do_plan()
+        else:
+            fork = torch.cuda.Event()
+            fork.record(main_stream)
+            side_stream.wait_event(fork)          # the previous step's Alg. 3 has read the state
+            s2o.s2o_attention_local(Qd, Kd, Vd, params, scratch=state, stream=side_stream)
+            join = torch.cuda.Event()
+            join.record(side_stream)
+            plan = do_plan()
+            main_stream.wait_event(join)
+        s2o.s2o_attention_prefix(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau, state, O=O,
+                                 computed=comp, skipped=skip)
         return plan
 
     def timed(fn, iters):
@@ -101,6 +172,12 @@ def main():
         torch.cuda.synchronize()
         return [ev[i].elapsed_time(ev[i + 1]) for i in range(iters)]
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.mul(src, 2.0, out=dst)          # one vectorized elementwise kernel: 1 GiB in, 1 GiB out
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step(args.tau)
     torch.cuda.synchronize()
@@ -110,24 +187,34 @@ def main():
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
-    # per-stage device time with events on the launch stream
-    plan_ms = float(np.mean(timed(lambda: s2o.s2o_plan(Qd, Kd, params, want_scores=False, scratch=scratch),
-                                  max(args.steps, 3))))
-    attn_fn = lambda tau: s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau, O=O,
-                                            computed=comp, skipped=skip, **akw)
-    attn_ms = float(np.mean(timed(lambda: attn_fn(args.tau), max(args.steps, 3))))
+    # per-stage device time, each stage alone, with events on the stream it is launched on
+    reps = max(args.steps, 3)
+    plan_ms = float(np.mean(timed(do_plan, reps)))
+    if args.fused:
+        attn_fn = lambda tau, out=O: s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau, O=out,
+                                                       computed=comp, skipped=skip, two_pass=False)
+        local_ms = None
+        attn_ms = prefix_ms = float(np.mean(timed(lambda: attn_fn(args.tau), reps)))
+    else:
+        local_ms = float(np.mean(timed(lambda: s2o.s2o_attention_local(Qd, Kd, Vd, params, scratch=state), reps)))
+        attn_fn = lambda tau, out=O: s2o.s2o_attention_prefix(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau,
+                                                              state, O=out, computed=comp, skipped=skip)
+        prefix_ms = float(np.mean(timed(lambda: attn_fn(args.tau), reps)))
+        attn_ms = local_ms + prefix_ms
     c, s = comp.cpu().numpy(), skip.cpu().numpy()
     flops, trig = tile_flops(w, c, s)
-    from oracle.s2o_oracle import density as density_of
-    dens = float(density_of(s, w.L, w.S, w.BM, w.BN).mean())
+    local_flops = local_tile_flops(w)
+    dens = float(density_of(w, s).mean())
     tflops = flops / (attn_ms * 1e-3) / 1e12
+    # the dominant kernel: the prefix walk (everything, in the fused form)
+    dom_flops = flops if args.fused else flops - local_flops
+    dom_tflops = dom_flops / (prefix_ms * 1e-3) / 1e12
 
     extra = {}
     if not args.no_mse:
         O_tau = O.float()
         Od = torch.empty_like(O)
-        dense_ms = float(np.mean(timed(lambda: s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm,
-                                                                 0.0, O=Od, **akw), 2)))
+        dense_ms = float(np.mean(timed(lambda: attn_fn(0.0, Od), 2))) + (local_ms or 0.0)
         ref = Od.float()
         per_head = ((O_tau - ref) ** 2).mean(dim=(0, 2, 3))
         extra["mse_vs_dense"] = float(per_head.mean())
@@ -139,10 +226,10 @@ def main():
     if args.sweep:
         sweep = []
         for tau in w.taus:
-            ms = float(np.mean(timed(lambda: attn_fn(tau), 3)))
+            ms = float(np.mean(timed(lambda: attn_fn(tau), 3))) + (local_ms or 0.0)
             cc, ss = comp.cpu().numpy(), skip.cpu().numpy()
             f, _ = tile_flops(w, cc, ss)
-            sweep.append(dict(tau=tau, attn_ms=ms, density=float(density_of(ss, w.L, w.S, w.BM, w.BN).mean()),
+            sweep.append(dict(tau=tau, attn_ms=ms, density=float(density_of(w, ss).mean()),
                               tflops=f / (ms * 1e-3) / 1e12))
         extra["tau_sweep"] = sweep
 
@@ -158,14 +245,20 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: Z={w.Z} H={w.H} Hkv={w.Hkv} L={w.L} D={w.D} S={w.S} "
                                f"tiles {w.BM}x{w.BN} tau={args.tau} stop_mode=0 seed={w.seed}"},
-        "plan_ms": plan_ms, "attn_ms": attn_ms, "density": dens, "sparsity": 1 - dens,
+        "plan_ms": plan_ms, "attn_ms": attn_ms, "attn_local_ms": local_ms, "attn_prefix_ms": prefix_ms,
+        "attn_local_tflops": None if local_ms is None else local_flops / (local_ms * 1e-3) / 1e12,
+        "streams": 1 if side_stream is None else 2, "density": dens, "sparsity": 1 - dens,
         "tflops_on_computed_blocks": tflops, "triggering_tiles": trig,
         "plan_algorithmic_GBps": plan_bytes(w) / (plan_ms * 1e-3) / 1e9,
         "plan_frac_of_hbm_peak": plan_bytes(w) / (plan_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "input_generation_s": t_gen,
-        "roofline": {"bound": "mfma", "kernel": "s2o_attention_kernel", "achieved": tflops,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
-                     "traffic": None},
+        "roofline": {"bound": "mfma",
+                     "kernel": "s2o_attention_kernel<0> (fused)" if args.fused else "s2o_attention_kernel<2> (prefix walk)",
+                     "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": dom_tflops / PEAK_BF16_TFLOPS, "ms_per_launch": prefix_ms,
+                     "flops_per_launch": dom_flops,
+                     "traffic": None if args.fused else recorded_traffic(w.name, args.tau, w.BM,
+                                                                         "s2o_attention_kernel<2>")},
         "cpu_baseline": cpu,
     }
     out.update(extra)
@@ -182,8 +275,8 @@ def cpu_baseline(w, Qb, Kb, Vb, plan, tau, issued_tiles_gpu):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    heads = sorted({0, w.H // 6, (2 * w.H) // 5, (4 * w.H) // 7, (5 * w.H) // 6, w.H - 1})
-    segs = sorted({min(1, w.N - 1), w.N // 8, w.N // 4, w.N // 2, (3 * w.N) // 4, w.N - 1})
+    heads = sorted({(i * (w.H - 1)) // 7 for i in range(8)})
+    segs = sorted({min(1, w.N - 1)} | {(i * (w.N - 1)) // 8 for i in range(1, 9)})
     G = w.G
     qp = plan.q_perm.cpu().numpy()
     kp = plan.kv_perm.cpu().numpy()

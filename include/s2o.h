@@ -120,14 +120,30 @@ int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* 
  *            Either may be NULL.
  *   scratch  NULL: one fused launch (the own-segment window and the prefix walk share
  *            registers).  Otherwise a device buffer, 256-byte aligned, of at least the size
- *            s2o_attention_sizes reports: the two passes of the paper are launched
- *            separately (Alg. 2 in original query order, its state kept in `scratch`, then
- *            Alg. 3), which computes only the causal own-segment tiles.  Both forms give the
- *            same result up to rounding order.  Ignored if use_q_perm == 0 and NULL. */
+ *            s2o_attention_sizes reports (else S2O_ESCRATCH): the call is then
+ *            s2o_attention_local followed by s2o_attention_prefix on `stream`.  Both forms
+ *            give the same result up to rounding order; the second does less own-segment work. */
 int s2o_attention(const void* Q, const void* K, const void* V, const s2o_params* params,
                   const int32_t* q_perm, const int32_t* kv_perm, float tau, void* O,
                   int32_t* computed, int32_t* skipped, void* scratch, size_t scratch_bytes,
                   void* stream);
+
+/* Pass 1 alone (Alg. 2): dense causal attention of every query over its own segment, queries
+ * in original order, written as un-normalised online-softmax state into `scratch`
+ * (required; the A / Lbuf / Mbuf buffers of the paper: per row (z,h,l) an fp32 accumulator
+ * [D] in a kernel-private element order, the normaliser l and the reference maximum m in
+ * base-2 logit units; layout: all accumulators, then all l, then all m).  It needs neither map,
+ * so it may run before, or on another stream beside, s2o_plan. */
+int s2o_attention_local(const void* Q, const void* K, const void* V, const s2o_params* params,
+                        void* scratch, size_t scratch_bytes, void* stream);
+
+/* Pass 2 alone (Alg. 3; Alg. 4's walk when use_q_perm == 0): resumes each row from the state
+ * s2o_attention_local left in `scratch` (read only; the caller orders the two calls), walks
+ * the prefix as described under s2o_attention, normalises and writes O and the counts. */
+int s2o_attention_prefix(const void* Q, const void* K, const void* V, const s2o_params* params,
+                         const int32_t* q_perm, const int32_t* kv_perm, float tau, void* O,
+                         int32_t* computed, int32_t* skipped, const void* scratch, size_t scratch_bytes,
+                         void* stream);
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libs2o.so")
 S2O_OK, S2O_EINVAL, S2O_EUNSUPPORTED, S2O_ESCRATCH, S2O_EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("s2o_version", "s2o_strerror", "s2o_last_hip_error", "s2o_plan_sizes", "s2o_plan",
-           "s2o_attention_sizes", "s2o_attention")
+           "s2o_attention_sizes", "s2o_attention", "s2o_attention_local", "s2o_attention_prefix")
 
 
 class S2OParams(C.Structure):
@@ -68,6 +68,11 @@ def load_library():
     lib.s2o_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(S2OParams),
                                   C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p,
                                   C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.s2o_attention_prefix.restype = C.c_int
+    lib.s2o_attention_prefix.argtypes = lib.s2o_attention.argtypes
+    lib.s2o_attention_local.restype = C.c_int
+    lib.s2o_attention_local.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(S2OParams),
+                                        C.c_void_p, C.c_size_t, C.c_void_p]
     _lib = lib
     return lib
 
@@ -130,9 +135,11 @@ class Plan:
     k_guide: "object" = None
 
 
-def s2o_plan(Q, K, params: S2OParams, want_scores: bool = True, scratch=None, stream=None) -> Plan:
+def s2o_plan(Q, K, params: S2OParams, want_scores: bool = True, scratch=None, stream=None,
+             maps=None) -> Plan:
     """Step 1.  Q, K: torch CUDA bf16 tensors [Z,H,L,D] / [Z,Hkv,L,D].  Returns device
-    tensors; the call is asynchronous on the current (or given) torch stream."""
+    tensors; the call is asynchronous on the current (or given) torch stream.
+    maps: optional (q_perm [Z,H,N,S], kv_perm [Z,H,max(P,4)]) int32 tensors to write into."""
     import torch
     lib = load_library()
     sz = s2o_plan_sizes(params)
@@ -141,8 +148,14 @@ def s2o_plan(Q, K, params: S2OParams, want_scores: bool = True, scratch=None, st
                           params.head_dim, params.seg_len)
     N = L // S
     P = S * N * (N - 1) // 2
-    out = Plan(q_perm=torch.empty((Z, H, N, S), dtype=torch.int32, device=dev),
-               kv_perm=torch.empty((Z, H, max(P, 4)), dtype=torch.int32, device=dev))
+    if maps is not None:
+        out = Plan(q_perm=maps[0], kv_perm=maps[1])
+        if (out.q_perm.numel() != Z * H * N * S or out.kv_perm.numel() != Z * H * max(P, 4)
+                or out.q_perm.dtype != torch.int32 or out.kv_perm.dtype != torch.int32):
+            raise ValueError("maps: wrong size or dtype")
+    else:
+        out = Plan(q_perm=torch.empty((Z, H, N, S), dtype=torch.int32, device=dev),
+                   kv_perm=torch.empty((Z, H, max(P, 4)), dtype=torch.int32, device=dev))
     if want_scores:
         out.s_q = torch.empty((Z, H, N, S), dtype=torch.float32, device=dev)
         out.s_k = torch.empty((Z, H, max(P, 4)), dtype=torch.float32, device=dev)
@@ -190,4 +203,35 @@ def s2o_attention(Q, K, V, params: S2OParams, q_perm, kv_perm, tau: float, O=Non
                              _ptr(q_perm), _ptr(kv_perm), float(tau), O.data_ptr(),
                              computed.data_ptr(), skipped.data_ptr(), _ptr(scratch),
                              0 if scratch is None else scratch.numel(), _stream_handle(stream)))
+    return O, computed, skipped
+
+
+def s2o_attention_local(Q, K, V, params: S2OParams, scratch=None, stream=None):
+    """Pass 1 (Alg. 2) alone.  Returns the state buffer (uint8 tensor) s2o_attention_prefix reads."""
+    import torch
+    lib = load_library()
+    if scratch is None:
+        scratch = torch.empty(s2o_attention_sizes(params)["scratch"], dtype=torch.uint8, device=Q.device)
+    _check(lib.s2o_attention_local(Q.data_ptr(), K.data_ptr(), V.data_ptr(), C.byref(params),
+                                   scratch.data_ptr(), scratch.numel(), _stream_handle(stream)))
+    return scratch
+
+
+def s2o_attention_prefix(Q, K, V, params: S2OParams, q_perm, kv_perm, tau: float, scratch, O=None,
+                         computed=None, skipped=None, stream=None):
+    """Pass 2 (Alg. 3) alone, resuming from the state s2o_attention_local left in `scratch`."""
+    import torch
+    lib = load_library()
+    dev = Q.device
+    Z, H, L, D = params.batch, params.q_heads, params.seq_len, params.head_dim
+    if O is None:
+        O = torch.empty((Z, H, L, D), dtype=torch.bfloat16, device=dev)
+    if computed is None:
+        computed = torch.empty((Z, H, L // params.block_m), dtype=torch.int32, device=dev)
+    if skipped is None:
+        skipped = torch.empty((Z, H, L // params.block_m), dtype=torch.int32, device=dev)
+    _check(lib.s2o_attention_prefix(Q.data_ptr(), K.data_ptr(), V.data_ptr(), C.byref(params),
+                                    _ptr(q_perm), _ptr(kv_perm), float(tau), O.data_ptr(),
+                                    computed.data_ptr(), skipped.data_ptr(), scratch.data_ptr(),
+                                    scratch.numel(), _stream_handle(stream)))
     return O, computed, skipped

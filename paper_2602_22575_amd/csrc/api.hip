@@ -131,31 +131,38 @@ int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* 
   return S2O_OK;
 }
 
-int s2o_attention(const void* Q, const void* K, const void* V, const s2o_params* params,
-                  const int32_t* q_perm, const int32_t* kv_perm, float tau, void* O,
-                  int32_t* computed, int32_t* skipped, void* scratch, size_t scratch_bytes,
-                  void* stream) {
+namespace {
+// passes: 1 = own-segment window into the state buffers (Alg. 2), 2 = prefix walk from them
+// (Alg. 3), 3 = both; 0 = both in one fused launch without state buffers.
+int attention_call(int passes, const void* Q, const void* K, const void* V, const s2o_params* params,
+                   const int32_t* q_perm, const int32_t* kv_perm, float tau, void* O,
+                   int32_t* computed, int32_t* skipped, void* scratch, size_t scratch_bytes,
+                   void* stream) {
   Shape s;
   const int rc = check_params(params, &s);
   if (rc != S2O_OK) return rc;
-  if (!Q || !K || !V || !O) return S2O_EINVAL;
-  if (params->use_q_perm && !q_perm) return S2O_EINVAL;
-  if (s.N > 1 && !kv_perm) return S2O_EINVAL;
-  if (tau != tau) return S2O_EINVAL;
-  if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(O, 16) ||
-      misaligned(kv_perm, 16))
-    return S2O_EINVAL;
-  if (scratch && (misaligned(scratch, 256) || scratch_bytes < s2o::attention_state_bytes(s.Z, s.H, s.L)))
+  const bool walk = passes != 1;            // the prefix walk is part of this call
+  if (!Q || !K || !V) return S2O_EINVAL;
+  if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16)) return S2O_EINVAL;
+  if (walk) {
+    if (!O || misaligned(O, 16)) return S2O_EINVAL;
+    if (params->use_q_perm && !q_perm) return S2O_EINVAL;
+    if (s.N > 1 && (!kv_perm || misaligned(kv_perm, 16))) return S2O_EINVAL;
+    if (tau != tau) return S2O_EINVAL;
+  }
+  if (passes != 0 &&
+      (!scratch || misaligned(scratch, 256) || scratch_bytes < s2o::attention_state_bytes(s.Z, s.H, s.L)))
     return S2O_ESCRATCH;
 
   s2o::AttnArgs a;
   memset(&a, 0, sizeof(a));
+  a.passes = passes;
   a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
   a.O = (uint16_t*)O;
   a.q_perm = q_perm; a.kv_perm = kv_perm; a.computed = computed; a.skipped = skipped;
   a.Z = s.Z; a.H = s.H; a.Hkv = s.Hkv; a.L = s.L; a.S = s.S; a.N = s.N;
   a.BM = params->block_m;
-  if (scratch) {
+  if (passes != 0) {
     const size_t rows = (size_t)s.Z * s.H * s.L;
     a.st_acc = (float*)scratch;
     a.st_l = a.st_acc + rows * s.D;
@@ -170,6 +177,29 @@ int s2o_attention(const void* Q, const void* K, const void* V, const s2o_params*
   }
   const hipError_t e = s2o::launch_attention(a, (hipStream_t)stream);
   return e == hipSuccess ? S2O_OK : hip_fail(e);
+}
+}  // namespace
+
+int s2o_attention(const void* Q, const void* K, const void* V, const s2o_params* params,
+                  const int32_t* q_perm, const int32_t* kv_perm, float tau, void* O,
+                  int32_t* computed, int32_t* skipped, void* scratch, size_t scratch_bytes,
+                  void* stream) {
+  return attention_call(scratch ? 3 : 0, Q, K, V, params, q_perm, kv_perm, tau, O, computed, skipped,
+                        scratch, scratch_bytes, stream);
+}
+
+int s2o_attention_local(const void* Q, const void* K, const void* V, const s2o_params* params,
+                        void* scratch, size_t scratch_bytes, void* stream) {
+  return attention_call(1, Q, K, V, params, nullptr, nullptr, 0.f, nullptr, nullptr, nullptr, scratch,
+                        scratch_bytes, stream);
+}
+
+int s2o_attention_prefix(const void* Q, const void* K, const void* V, const s2o_params* params,
+                         const int32_t* q_perm, const int32_t* kv_perm, float tau, void* O,
+                         int32_t* computed, int32_t* skipped, const void* scratch, size_t scratch_bytes,
+                         void* stream) {
+  return attention_call(2, Q, K, V, params, q_perm, kv_perm, tau, O, computed, skipped,
+                        const_cast<void*>(scratch), scratch_bytes, stream);
 }
 
 }  // extern "C"

@@ -533,11 +533,11 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
   const int64_t blocks = (int64_t)a.Z * a.H * a.N * JG;
   if (blocks <= 0 || blocks > 0x7fffffff) return hipErrorInvalidValue;
   const dim3 grid((unsigned)blocks), block(kThreads);
-  if (a.st_acc == nullptr) {
+  if (a.passes == 0) {
     hipLaunchKernelGGL(s2o_attention_kernel<0>, grid, block, kAttnLds, stream, a);
   } else {
-    hipLaunchKernelGGL(s2o_attention_kernel<1>, grid, block, kAttnLds, stream, a);
-    hipLaunchKernelGGL(s2o_attention_kernel<2>, grid, block, kAttnLds, stream, a);
+    if (a.passes & 1) hipLaunchKernelGGL(s2o_attention_kernel<1>, grid, block, kAttnLds, stream, a);
+    if (a.passes & 2) hipLaunchKernelGGL(s2o_attention_kernel<2>, grid, block, kAttnLds, stream, a);
   }
   return hipGetLastError();
 }

@@ -17,7 +17,8 @@ struct AttnArgs {
   const int32_t* kv_perm;
   int32_t* computed;
   int32_t* skipped;
-  float* st_acc;  // two-pass state (NULL: one fused launch): [Z*H*L][128], then l and m [Z*H*L]
+  int passes;     // 0: one fused launch; bit 0: Alg. 2 into the state buffers; bit 1: Alg. 3 from them
+  float* st_acc;  // state buffers: acc [Z*H*L][128], then l and m [Z*H*L]
   float* st_l;
   float* st_m;
   int Z, H, Hkv, L, S, N;

@@ -143,6 +143,30 @@ def test_determinism(tiny):
         assert np.array_equal(x, y)
 
 
+def test_separate_passes_equal_the_combined_call(tiny):
+    """s2o_attention_local + s2o_attention_prefix (the local pass issued before the plan, as a
+    caller overlapping the two would) give bit-identical results to s2o_attention with a
+    state buffer, and agree with the single fused launch within the output tolerance."""
+    import torch
+    import paper_2602_22575_amd as s2o
+    w, (Qb, Kb, Vb), (Qd, Kd, Vd) = tiny
+    p = gu.params_for(w)
+    _say("case: tiny separate passes")
+    state = s2o.s2o_attention_local(Qd, Kd, Vd, p)
+    plan = s2o.s2o_plan(Qd, Kd, p, want_scores=False)
+    O1, c1, s1 = s2o.s2o_attention_prefix(Qd, Kd, Vd, p, plan.q_perm, plan.kv_perm, 0.05, state)
+    O2, c2, s2_ = s2o.s2o_attention(Qd, Kd, Vd, p, plan.q_perm, plan.kv_perm, 0.05, two_pass=True)
+    O3, c3, s3 = s2o.s2o_attention(Qd, Kd, Vd, p, plan.q_perm, plan.kv_perm, 0.05, two_pass=False)
+    torch.cuda.synchronize()
+    assert torch.equal(O1.view(torch.int16), O2.view(torch.int16))
+    assert torch.equal(c1, c2) and torch.equal(s1, s2_)
+    assert (O1.float() - O3.float()).abs().max().item() <= parity.O_MAX_ABS
+    # the state buffer is only read by the second pass: running it again reproduces the result
+    O4, c4, s4 = s2o.s2o_attention_prefix(Qd, Kd, Vd, p, plan.q_perm, plan.kv_perm, 0.05, state)
+    torch.cuda.synchronize()
+    assert torch.equal(O1.view(torch.int16), O4.view(torch.int16)) and torch.equal(c1, c4)
+
+
 @pytest.mark.parametrize("L,S,H,Hkv", [(256, 256, 1, 1), (128, 64, 2, 1), (1536, 192, 4, 2), (2048, 1024, 2, 2)])
 def test_edge_shapes(gpu, L, S, H, Hkv):
     """Single segment (no prefix at all), a one-tile segment (three idle wavefronts), a
