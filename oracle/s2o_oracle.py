@@ -31,6 +31,7 @@ Readings of points the paper leaves open (each also listed in the design notes):
   * Triggering tile: stop_mode 0 discards it (Alg. 3 / Alg. 4 break before committing);
     stop_mode 1 commits it and then stops (the deferred check of the appendix kernel D).
     PARITY UNPINNED between the two; each is pinned by the visited-set identity.
+    stop_mode 2 evaluates no stop rule (the appendix's kernel C: ranked gather only).
   * Argsort tie-break: stable, equal scores keep ascending index; -0 == +0.
   * GQA: K/V head = h // G; k_guide per KV head; q_mean and both maps per query head.
   * Ranking scores are raw dot products (no softmax scale); attention uses
@@ -190,7 +191,7 @@ def pass1(q, k, v, scale, BM, BN):
 
 
 def attention(Q, K, V, q_perm, kv_perm, S, BM, BN, tau, stop_mode=0, scale=None,
-              forced_computed=None, heads=None, segments=None, return_gain=False):
+              forced_computed=None, heads=None, segments=None, return_gain=False, max_tiles=None):
     """Alg. 2 + Alg. 3.  Returns (O [Z,H,L,D] float64, computed int32 [Z,H,L/BM],
     skipped int32 [Z,H,L/BM]); counts are indexed by permuted tile: entry n*(S/BM)+j is
     the j-th tile of Q~_n.
@@ -198,6 +199,12 @@ def attention(Q, K, V, q_perm, kv_perm, S, BM, BN, tau, stop_mode=0, scale=None,
     forced_computed: replay mode -- tile j folds in exactly the first forced_computed[j]
       prefix tiles of its row (same layout as `computed`) and the stop rule is not
       evaluated; skipped is then reported as the remainder.
+    max_tiles: fixed budget (the top-k selection of the appendix's matched-sparsity
+      comparison, "Why Online Permutation Adds Negligible Overhead"): a query tile visits
+      at most the first max_tiles tiles of its ranked row; the stop rule still applies
+      inside the budget, and stop_mode 2 (no stop rule at all, the appendix's kernel C)
+      makes it visit exactly min(max_tiles, n*S/B_N).  skipped counts every tile never
+      issued, budgeted-out ones included.
     heads / segments: optional subsets (others are left zero) for sampled checks.
     return_gain: also return a dict {(z,h,n): array [S/BM, n*S/BN]} of max-row gains for
       the tiles that were evaluated (nan elsewhere)."""
@@ -228,14 +235,15 @@ def attention(Q, K, V, q_perm, kv_perm, S, BM, BN, tau, stop_mode=0, scale=None,
                     st = (m[r], l[r], acc[r])
                     forced = None if forced_computed is None else int(forced_computed[z, h, n * TJ + j])
                     committed, issued = 0, 0
-                    for kt in range(nK if forced is None else forced):
+                    budget = nK if max_tiles is None else min(nK, int(max_tiles))
+                    for kt in range(budget if forced is None else forced):
                         T = row[kt * BN:(kt + 1) * BN]
                         x = scale * (qt[r] @ k_all[T].T)
                         cand, mass, prev = online_softmax_update(st, x, v_all[T])
                         gain = float((mass / prev).max())
                         gn[j, kt] = gain
                         issued += 1
-                        stop = forced is None and gain < tau
+                        stop = forced is None and stop_mode != 2 and gain < tau
                         if stop and stop_mode == 0:
                             break                                   # triggering tile dropped
                         st = cand

@@ -265,6 +265,47 @@ def test_exhaustive_tiny_cases_against_literal_model():
     assert checked > 5000
 
 
+def test_tile_budget_is_masked_softmax_over_the_first_k_ranked_tiles():
+    """Fixed budget with no stop rule (top-k selection on the ranked order): the output is
+    plain softmax attention under an explicit L x L mask -- own-segment causal keys plus the
+    first k*B_N entries of the segment's ranked row -- built here without the oracle."""
+    Z, H, Hkv, L, D, S, BM, BN = 1, 2, 1, 96, 8, 16, 8, 4
+    Q, K, V = rand_qkv(Z, H, Hkv, L, D, scale=1.3)
+    p = orc.plan(Q, K, S)
+    scale = 1.0 / math.sqrt(D)
+    for k in (0, 1, 3, 7, 1000):
+        O, comp, skip = orc.attention(Q, K, V, p["q_perm"], p["kv_perm"], S, BM, BN, tau=0.5, stop_mode=2,
+                                      max_tiles=k)
+        for h in range(H):
+            x = scale * (Q[0, h] @ K[0, 0].T)
+            allow = np.zeros((L, L), dtype=bool)
+            for n in range(L // S):
+                rows = slice(n * S, (n + 1) * S)
+                own = np.tril(np.ones((S, S), dtype=bool))
+                allow[rows, n * S:(n + 1) * S] = own
+                row = p["kv_perm"][0, h, orc.kv_row_offset(n, S):orc.kv_row_offset(n, S) + n * S]
+                allow[rows, row[:min(k, n * S // BN) * BN]] = True
+            w = scipy_softmax(np.where(allow, x, -np.inf), axis=1)
+            np.testing.assert_allclose(O[0, h], w @ V[0, 0], atol=1e-12)
+        nK = orc.prefix_tiles(L, S, BM, BN)
+        assert np.array_equal(comp[0, 0], np.minimum(nK, k)) and np.array_equal(skip[0, 0], nK - np.minimum(nK, k))
+    # a budget that is never reached changes nothing; a stop inside the budget is the usual stop
+    for stop_mode in (0, 1):
+        ref = orc.attention(Q, K, V, p["q_perm"], p["kv_perm"], S, BM, BN, 0.05, stop_mode)
+        big = orc.attention(Q, K, V, p["q_perm"], p["kv_perm"], S, BM, BN, 0.05, stop_mode, max_tiles=10 ** 6)
+        for a, b in zip(ref, big):
+            assert np.array_equal(a, b)
+        cut = orc.attention(Q, K, V, p["q_perm"], p["kv_perm"], S, BM, BN, 0.05, stop_mode, max_tiles=2)
+        nK = orc.prefix_tiles(L, S, BM, BN)
+        issued_ref, issued_cut = nK - ref[2][0], nK - cut[2][0]
+        assert np.array_equal(issued_cut, np.minimum(issued_ref, 2))
+        assert np.array_equal(cut[1][0], np.minimum(ref[1][0], 2))
+    # stop_mode 2 without a budget is dense attention whatever tau says
+    O, comp, skip = orc.attention(Q, K, V, p["q_perm"], p["kv_perm"], S, BM, BN, tau=10.0, stop_mode=2)
+    np.testing.assert_allclose(O, orc.dense_attention(Q, K, V), atol=1e-12)
+    assert np.all(skip == 0)
+
+
 def test_monotone_in_tau():
     Z, H, Hkv, L, D, S = 1, 2, 1, 96, 8, 16
     Q, K, V = rand_qkv(Z, H, Hkv, L, D, scale=1.5)
