@@ -38,7 +38,7 @@
 extern "C" {
 #endif
 
-#define S2O_VERSION 1
+#define S2O_VERSION 2
 
 enum {
   S2O_OK = 0,
@@ -55,13 +55,17 @@ typedef struct s2o_params {
   int32_t kv_heads;      /* Hkv, H % Hkv == 0                                              */
   int32_t seq_len;       /* L, L % seg_len == 0                                            */
   int32_t head_dim;      /* D, only 128                                                    */
-  int32_t seg_len;       /* S (paper default 2048), multiple of B_M, S <= 8192             */
+  int32_t seg_len;       /* S (paper default 2048), multiple of B_M; s2o_plan needs S <= 8192 */
   int32_t block_m;       /* B_M: query tile rows, 64 or 128                                */
   int32_t block_n;       /* B_N: key tile tokens, only 64                                  */
   int32_t use_q_perm;    /* 1: gather queries by Q_perm (Alg. 3); 0: original order (Alg. 4) */
   int32_t stop_mode;     /* 0: a triggering tile is discarded (Alg. 3/4 as printed);
-                            1: it is folded in, then the walk stops (deferred check, App. A) */
+                            1: it is folded in, then the walk stops (deferred check, App. A);
+                            2: no stop rule is evaluated at all (App. A, kernel C)         */
   float softmax_scale;   /* 0 -> 1/sqrt(D)                                                 */
+  int32_t max_prefix_tiles; /* 0: no budget; k > 0: a query tile visits at most the first k
+                            tiles of its ranked prefix row (top-k selection, App. A)       */
+  int32_t reserved;      /* must be 0                                                      */
   int64_t q_stride[3];   /* element strides of Q for (z, h, l); all 0 -> packed [Z,H,L,D]  */
   int64_t k_stride[3];
   int64_t v_stride[3];
@@ -117,7 +121,7 @@ int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* 
  *   computed [Z,H,L/B_M] prefix tiles folded into the output of permuted query tile
  *            n*(S/B_M)+j; skipped: prefix tiles never loaded.  n*S/B_N - computed - skipped
  *            is 1 when a triggering tile was loaded and discarded (stop_mode 0), else 0.
- *            Either may be NULL.
+ *            Tiles beyond max_prefix_tiles count as skipped.  Either may be NULL.
  *   scratch  NULL: one fused launch (the own-segment window and the prefix walk share
  *            registers).  Otherwise a device buffer, 256-byte aligned, of at least the size
  *            s2o_attention_sizes reports (else S2O_ESCRATCH): the call is then

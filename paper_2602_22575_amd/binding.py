@@ -24,6 +24,7 @@ class S2OParams(C.Structure):
                 ("kv_heads", C.c_int32), ("seq_len", C.c_int32), ("head_dim", C.c_int32),
                 ("seg_len", C.c_int32), ("block_m", C.c_int32), ("block_n", C.c_int32),
                 ("use_q_perm", C.c_int32), ("stop_mode", C.c_int32), ("softmax_scale", C.c_float),
+                ("max_prefix_tiles", C.c_int32), ("reserved", C.c_int32),
                 ("q_stride", C.c_int64 * 3), ("k_stride", C.c_int64 * 3),
                 ("v_stride", C.c_int64 * 3), ("o_stride", C.c_int64 * 3)]
 
@@ -88,12 +89,13 @@ def _check(rc: int):
 
 def make_params(Z, H, Hkv, L, D, S, BM=64, BN=64, use_q_perm=1, stop_mode=0, softmax_scale=0.0,
                 q_stride=(0, 0, 0), k_stride=(0, 0, 0), v_stride=(0, 0, 0),
-                o_stride=(0, 0, 0)) -> S2OParams:
+                o_stride=(0, 0, 0), max_prefix_tiles=0) -> S2OParams:
     p = S2OParams()
     p.struct_size = C.sizeof(S2OParams)
     p.batch, p.q_heads, p.kv_heads, p.seq_len, p.head_dim = Z, H, Hkv, L, D
     p.seg_len, p.block_m, p.block_n = S, BM, BN
     p.use_q_perm, p.stop_mode, p.softmax_scale = use_q_perm, stop_mode, softmax_scale
+    p.max_prefix_tiles, p.reserved = max_prefix_tiles, 0
     for name, val in (("q_stride", q_stride), ("k_stride", k_stride), ("v_stride", v_stride),
                       ("o_stride", o_stride)):
         setattr(p, name, (C.c_int64 * 3)(*val))

@@ -35,7 +35,7 @@ bool fill_strides(const int64_t in[3], int64_t out[3], int heads, int L, int D) 
   return out[2] >= D;
 }
 
-int check_params(const s2o_params* p, Shape* s) {
+int check_params(const s2o_params* p, Shape* s, bool for_plan = false) {
   if (!p) return S2O_EINVAL;
   if (p->struct_size != (int32_t)sizeof(s2o_params)) return S2O_EINVAL;
   if (p->batch <= 0 || p->q_heads <= 0 || p->kv_heads <= 0 || p->seq_len <= 0 || p->seg_len <= 0)
@@ -43,11 +43,13 @@ int check_params(const s2o_params* p, Shape* s) {
   if (p->q_heads % p->kv_heads != 0) return S2O_EINVAL;
   if (p->seq_len % p->seg_len != 0) return S2O_EINVAL;
   if (p->use_q_perm != 0 && p->use_q_perm != 1) return S2O_EINVAL;
-  if (p->stop_mode != 0 && p->stop_mode != 1) return S2O_EINVAL;
+  if (p->stop_mode < 0 || p->stop_mode > 2) return S2O_EINVAL;
+  if (p->max_prefix_tiles < 0 || p->reserved != 0) return S2O_EINVAL;
   if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) return S2O_EINVAL;
   if (p->head_dim != 128) return S2O_EUNSUPPORTED;
   if ((p->block_m != 64 && p->block_m != 128) || p->block_n != 64) return S2O_EUNSUPPORTED;
-  if (p->seg_len % p->block_m != 0 || p->seg_len > 8192) return S2O_EUNSUPPORTED;
+  if (p->seg_len % p->block_m != 0) return S2O_EUNSUPPORTED;
+  if (for_plan && p->seg_len > 8192) return S2O_EUNSUPPORTED;   // a segment's query scores are sorted in LDS
   if ((int64_t)p->batch * p->q_heads * (p->seq_len / p->seg_len) > (1 << 24)) return S2O_EUNSUPPORTED;
   s->Z = p->batch; s->H = p->q_heads; s->Hkv = p->kv_heads; s->L = p->seq_len;
   s->D = p->head_dim; s->S = p->seg_len; s->N = p->seq_len / p->seg_len;
@@ -70,7 +72,7 @@ const char* s2o_strerror(int code) {
   switch (code) {
     case S2O_OK: return "ok";
     case S2O_EINVAL: return "invalid argument";
-    case S2O_EUNSUPPORTED: return "unsupported configuration (need D=128, B_M in {64,128}, B_N=64, S%B_M==0, S<=8192)";
+    case S2O_EUNSUPPORTED: return "unsupported configuration (need D=128, B_M in {64,128}, B_N=64, S%B_M==0; s2o_plan: S<=8192)";
     case S2O_ESCRATCH: return "scratch buffer missing, misaligned or too small";
     case S2O_EHIP: return "HIP runtime error (see s2o_last_hip_error)";
     default: return "unknown error code";
@@ -83,7 +85,7 @@ int s2o_plan_sizes(const s2o_params* params, size_t* q_perm_bytes, size_t* kv_pe
                    size_t* s_q_bytes, size_t* s_k_bytes, size_t* q_mean_bytes,
                    size_t* k_guide_bytes, size_t* scratch_bytes) {
   Shape s;
-  const int rc = check_params(params, &s);
+  const int rc = check_params(params, &s, true);
   if (rc != S2O_OK) return rc;
   const size_t zh = (size_t)s.Z * s.H;
   const size_t P = (size_t)s2o::kv_row_offset(s.N, s.S);
@@ -100,7 +102,7 @@ int s2o_plan_sizes(const s2o_params* params, size_t* q_perm_bytes, size_t* kv_pe
 int s2o_plan(const void* Q, const void* K, const s2o_params* params, const s2o_plan_out* out,
              void* scratch, size_t scratch_bytes, void* stream) {
   Shape s;
-  const int rc = check_params(params, &s);
+  const int rc = check_params(params, &s, true);
   if (rc != S2O_OK) return rc;
   if (!Q || !K || !out || !out->q_perm) return S2O_EINVAL;
   if (s.N > 1 && !out->kv_perm) return S2O_EINVAL;
@@ -169,6 +171,7 @@ int attention_call(int passes, const void* Q, const void* K, const void* V, cons
     a.st_m = a.st_l + rows;
   }
   a.use_q_perm = params->use_q_perm; a.stop_mode = params->stop_mode;
+  a.max_tiles = params->max_prefix_tiles;
   a.tau = tau;
   const float scale = params->softmax_scale > 0.f ? params->softmax_scale : 1.0f / sqrtf((float)s.D);
   a.scale_log2e = scale * 1.4426950408889634f;

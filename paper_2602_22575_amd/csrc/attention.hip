@@ -125,7 +125,9 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   const int64_t zh = (int64_t)z * a.H + h;
   const int32_t* kvrow = a.kv_perm + zh * kv_row_offset(a.N, a.S) + kv_row_offset(n, a.S);
   const int nS = n * a.S;
-  const int nK = PASS == 1 ? 0 : nS / kBN;     // prefix tiles this launch walks
+  const int nK_all = nS / kBN;                 // prefix tiles that exist for this segment
+  // prefix tiles this launch may walk: none in the own-segment pass, at most the budget
+  const int nK = PASS == 1 ? 0 : (a.max_tiles > 0 ? min(nK_all, a.max_tiles) : nK_all);
 
   // wavefront -> (query tile of the workgroup, 32-row part); the parts of a tile are
   // wavefronts tile, tile + tpw, ...
@@ -366,14 +368,17 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   // query tile has stopped (or that has no query tile) drops into a drain loop that only
   // keeps loading tiles for the others, so the hot loops carry no "am I still active" merges.
   int it = 0;
-  // ---- own-segment tiles (Pass-1): dense, causal mask, no stop rule
-  for (; it < nloc; ++it) {
+  // ---- tiles folded in unconditionally: the own-segment tiles (Pass-1: dense, causal mask)
+  // and, when no stop rule is asked for (stop_mode 2), the prefix tiles as well
+  const int nplain = a.stop_mode == 2 ? ntiles : nloc;
+  for (; it < nplain; ++it) {
     if (it + 1 < ntiles) load_tile(it + 1);
-    if (it * kBN <= wave_pmax) {       // wave_pmax = -1 for a wavefront without a query tile
+    const bool own = it < nloc;
+    if (own ? it * kBN <= wave_pmax : active) {   // wave_pmax = -1 for a wavefront without a query tile
       qk(it & 1);
       // the causal mask only matters if some row of the wavefront ends inside this tile
       // (never skipped for permuted rows, whose positions are scattered)
-      if (PASS == 1 && it * kBN + kBN - 1 <= wave_pmax - (kRowsPerWave - 1)) softmax(std::false_type{}, it);
+      if (!own || (PASS == 1 && it * kBN + kBN - 1 <= wave_pmax - (kRowsPerWave - 1))) softmax(std::false_type{}, it);
       else softmax(std::true_type{}, it);
       bf16x8 pb[4];
       pack_p(pb);
@@ -381,6 +386,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
       pv(it % 3, pb);
       l_run = prev + mass;
       m_ref = m_use;
+      if (!own) { ++committed; ++issued; }
     }
     __syncthreads();
   }
@@ -505,7 +511,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
       if (lane == 0 && part == 0) {
         const int64_t ci = zh * (a.L / BM) + (int64_t)n * TJ + j;
         if (a.computed) a.computed[ci] = committed;
-        if (a.skipped) a.skipped[ci] = nK - issued;
+        if (a.skipped) a.skipped[ci] = nK_all - issued;
       }
     }
   }

@@ -24,6 +24,7 @@ struct AttnArgs {
   int Z, H, Hkv, L, S, N;
   int BM;  // query tile rows (64 or 128); the key tile is 64 tokens
   int use_q_perm, stop_mode;
+  int max_tiles;  // > 0: a query tile visits at most this many prefix tiles
   float tau;
   float scale_log2e;  // softmax_scale * log2(e): logits are kept in base-2 units
   int64_t qs[3], ks[3], vs[3], os[3];

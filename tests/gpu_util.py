@@ -26,8 +26,8 @@ def gpu_plan(w, Qd, Kd):
     return out, {k: getattr(out, k).cpu().numpy() for k in ("q_perm", "kv_perm", "s_q", "s_k", "q_mean", "k_guide")}
 
 
-def gpu_attention(w, Qd, Kd, Vd, q_perm, kv_perm, tau, stop_mode=0, use_q_perm=1, two_pass=True):
-    p = params_for(w, stop_mode=stop_mode, use_q_perm=use_q_perm)
+def gpu_attention(w, Qd, Kd, Vd, q_perm, kv_perm, tau, stop_mode=0, use_q_perm=1, two_pass=True, max_tiles=0):
+    p = params_for(w, stop_mode=stop_mode, use_q_perm=use_q_perm, max_prefix_tiles=max_tiles)
     O, c, s = s2o.s2o_attention(Qd, Kd, Vd, p, q_perm, kv_perm, tau, two_pass=two_pass)
     torch.cuda.synchronize()
     return bits_of(O), c.cpu().numpy(), s.cpu().numpy()

@@ -141,10 +141,13 @@ def check_counts(gain_row, tau, stop_mode, computed, skipped):
 
 
 def check_attention(w, Qb, Kb, Vb, q_perm, kv_perm, tau, stop_mode, O_gpu_bits, computed, skipped,
-                    heads=None, segments=None, gains=None, use_q_perm=True):
+                    heads=None, segments=None, gains=None, use_q_perm=True, max_tiles=0):
     """Compares one s2o_attention result with the oracle run on the same maps, one query head
     (with its KV head) at a time.  Returns stats (robust/ambiguous tile counts, max-abs and
-    relative MSE of O) and the gain profiles (reusable for another tau)."""
+    relative MSE of O) and the gain profiles (reusable for another tau).
+    max_tiles > 0: the run had a tile budget -- the stop rule is checked on the first
+    max_tiles gains of each row and the tiles beyond the budget must be reported skipped.
+    stop_mode 2: no stop rule -- every tile inside the budget must be folded in."""
     S, N, BM, BN = w.S, w.N, w.BM, w.BN
     TJ = S // BM
     hs = list(range(w.H)) if heads is None else list(heads)
@@ -158,16 +161,21 @@ def check_attention(w, Qb, Kb, Vb, q_perm, kv_perm, tau, stop_mode, O_gpu_bits, 
             Q, K, V = to_f64(Qb[z:z + 1, h:h + 1]), to_f64(Kb[z:z + 1, g:g + 1]), to_f64(Vb[z:z + 1, g:g + 1])
             qp = q_perm[z:z + 1, h:h + 1] if use_q_perm else orc.identity_maps(1, 1, w.L, S)[0]
             kp = kv_perm[z:z + 1, h:h + 1]
-            if (z, h) not in gains:
+            if (z, h) not in gains and stop_mode != 2:
                 gains[(z, h)] = orc.gain_profile(Q, K, V, qp, kp, S, BM, BN, stop_mode=stop_mode, segments=ns)
-            gz = gains[(z, h)]
+            gz = gains.get((z, h))
             for n in ns:
                 for j in range(TJ):
                     c = int(computed[z, h, n * TJ + j]); s = int(skipped[z, h, n * TJ + j])
                     if n == 0:
                         assert (c, s) == (0, 0)
                         continue
-                    if check_counts(gz[(0, 0, n)][j], tau, stop_mode, c, s):
+                    nK = n * S // BN
+                    budget = min(nK, max_tiles) if max_tiles > 0 else nK
+                    if stop_mode == 2:
+                        assert (c, s) == (budget, nK - budget)
+                        robust += 1
+                    elif check_counts(gz[(0, 0, n)][j][:budget], tau, stop_mode, c, s - (nK - budget)):
                         robust += 1
                     else:
                         ambiguous += 1

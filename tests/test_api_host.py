@@ -23,11 +23,11 @@ def test_every_declared_symbol_is_exported(lib):
     assert declared == set(b.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.s2o_version() == 1
+    assert lib.s2o_version() == 2
 
 
 def test_struct_layout_matches_header(lib):
-    assert C.sizeof(b.S2OParams) == 12 * 4 + 12 * 8
+    assert C.sizeof(b.S2OParams) == 14 * 4 + 12 * 8
     assert C.sizeof(b.S2OPlanOut) == 6 * 8
 
 
@@ -55,7 +55,8 @@ def test_size_queries():
     (dict(BN=128), b.S2O_EUNSUPPORTED),
     (dict(S=96, L=960), b.S2O_EUNSUPPORTED),      # S % 64 != 0
     (dict(S=16384, L=32768), b.S2O_EUNSUPPORTED),
-    (dict(stop_mode=2), b.S2O_EINVAL),
+    (dict(stop_mode=3), b.S2O_EINVAL),
+    (dict(max_prefix_tiles=-1), b.S2O_EINVAL),
     (dict(use_q_perm=5), b.S2O_EINVAL),
     (dict(softmax_scale=-1.0), b.S2O_EINVAL),
     (dict(q_stride=(0, 0, 100)), b.S2O_EINVAL),   # row stride not 16-byte aligned / < D
@@ -66,6 +67,16 @@ def test_bad_params_are_rejected(kw, code):
     with pytest.raises(b.S2OError) as e:
         b.s2o_plan_sizes(b.make_params(**base))
     assert e.value.code == code
+
+
+def test_segment_length_limit_applies_to_the_plan_only():
+    """The ranking sorts a segment's query scores in LDS (S <= 8192); attention takes any S
+    (S = L is dense contiguous causal attention, the appendix's kernel A)."""
+    p = b.make_params(1, 4, 2, 32768, 128, 32768)
+    assert b.s2o_attention_sizes(p)["scratch"] == 4 * 32768 * 130 * 4
+    with pytest.raises(b.S2OError) as e:
+        b.s2o_plan_sizes(p)
+    assert e.value.code == b.S2O_EUNSUPPORTED
 
 
 def test_null_and_scratch_errors_come_before_any_hip_call(lib):

@@ -143,6 +143,57 @@ def test_determinism(tiny):
         assert np.array_equal(x, y)
 
 
+@pytest.mark.parametrize("two_pass", [True, False])
+def test_tiny_tile_budget_and_no_stop_mode(tiny, two_pass):
+    """Fixed budget of prefix tiles (top-k on the ranked order) alone (stop_mode 2), combined
+    with the stop rule, and stop_mode 2 without a budget (= dense whatever tau says)."""
+    w, (Qb, Kb, Vb), (Qd, Kd, Vd) = tiny
+    plan, pg = gu.gpu_plan(w, Qd, Kd)
+    Q, K, V = (parity.to_f64(x) for x in (Qb, Kb, Vb))
+    for k in (1, 3, 1000):
+        _say(f"case: tiny budget k={k} stop_mode=2 two_pass={two_pass}")
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, 0.3, 2, two_pass=two_pass, max_tiles=k)
+        st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], 0.3, 2, Ob, c, s, max_tiles=k)
+        ref, _, _ = orc.attention(Q, K, V, pg["q_perm"], pg["kv_perm"], w.S, w.BM, w.BN, 0.3, stop_mode=2, max_tiles=k)
+        assert np.abs(parity.to_f64(Ob) - ref).max() <= parity.O_MAX_ABS
+    gains = {(0, 0): orc.gain_profile(Q, K, V, pg["q_perm"], pg["kv_perm"], w.S, w.BM, w.BN, stop_mode=0)}
+    tau = parity.pick_tau(gains, 0.02)
+    for k in (2, 5):
+        _say(f"case: tiny budget k={k} with the stop rule, tau={tau}")
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, 0, two_pass=two_pass, max_tiles=k)
+        st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, 0, Ob, c, s, gains=gains,
+                                    max_tiles=k)
+        assert st["ambiguous"] == 0
+        co, so = orc.attention(Q, K, V, pg["q_perm"], pg["kv_perm"], w.S, w.BM, w.BN, tau, 0, max_tiles=k)[1:]
+        assert np.array_equal(c, co) and np.array_equal(s, so)
+    Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, 10.0, 2, two_pass=two_pass)
+    assert np.all(s == 0)
+    assert np.abs(parity.to_f64(Ob) - orc.dense_attention(Q, K, V)).max() <= parity.O_MAX_ABS
+
+
+def test_dense_contiguous_long_segment(gpu):
+    """S = L beyond the plan's segment limit: one segment, no prefix -- plain causal
+    attention over contiguous K/V (the appendix's kernel A), checked on sampled rows."""
+    import torch
+    import paper_2602_22575_amd as s2o
+    w = inputs.workload("llama8k", L=16384, S=16384, H=2, Hkv=1, seed=5)
+    _say("case: dense contiguous L=S=16384")
+    Qb, Kb, Vb = inputs.make_qkv(w)
+    Qd, Kd, Vd = (gu.to_dev(x) for x in (Qb, Kb, Vb))
+    p = gu.params_for(w, use_q_perm=0)
+    outs = []
+    for two_pass in (True, False):
+        O, c, s = s2o.s2o_attention(Qd, Kd, Vd, p, None, None, 0.0, two_pass=two_pass)
+        torch.cuda.synchronize()
+        assert int(c.abs().sum()) == 0 and int(s.abs().sum()) == 0
+        outs.append(parity.to_f64(gu.bits_of(O)))
+    rows = np.unique(np.concatenate([np.arange(0, 70), np.arange(8150, 8260), np.arange(16300, 16384),
+                                     np.random.default_rng(0).integers(0, 16384, 200)]))
+    ref = orc.dense_attention(parity.to_f64(Qb), parity.to_f64(Kb), parity.to_f64(Vb), rows=rows)
+    for O in outs:
+        assert np.abs(O[:, :, rows] - ref).max() <= parity.O_MAX_ABS
+
+
 def test_separate_passes_equal_the_combined_call(tiny):
     """s2o_attention_local + s2o_attention_prefix (the local pass issued before the plan, as a
     caller overlapping the two would) give bit-identical results to s2o_attention with a
