@@ -1,0 +1,119 @@
+#!/usr/bin/env python3
+"""Two measurement studies on one MI355X, printed as Markdown tables.
+
+  python -m paper_2602_22575_amd.studies abcd         overhead decomposition (paper App. A,
+      "Why Online Permutation Adds Negligible Overhead", kernels A-D): the same dense amount
+      of work, adding one mechanism at a time --
+        A  contiguous causal attention (S = L: one segment, no maps)
+        B  + indexed gather with identity maps          (stop_mode 2)
+        C  + ranked maps from s2o_plan                  (stop_mode 2)
+        D  + the early-stop vote, never stopping        (stop_mode 0, tau = -1)
+  python -m paper_2602_22575_amd.studies plan-table   ranking time over (L, S) (the paper's
+      retrieval-latency table in "Additional details on end-to-end operator performance"),
+      with time * S / L^2 to check the L^2 / S law.
+
+Inputs are the seeded synthetic workloads of inputs.py; every figure is the mean of a few
+launches timed with events on the launch stream.
+"""
+from __future__ import annotations
+
+import sys
+
+import numpy as np
+
+
+def _timed(fn, iters=3):
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+    ev[0].record()
+    for i in range(iters):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    return float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(iters)]))
+
+
+def _dev(bits):
+    import torch
+    return torch.from_numpy(bits.view(np.int16)).to("cuda:0").view(torch.bfloat16)
+
+
+def abcd():
+    import torch
+    from . import binding as s2o, inputs
+    print("| L | S | A contiguous ms (TFLOP/s) | B identity gather ms | C ranked gather ms | D + stop vote ms | B/A | C/B | D/C |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for name in ("llama8k", "llama32k", "llama128k"):
+        w = inputs.workload(name)
+        Qd, Kd, Vd = (_dev(x) for x in inputs.make_qkv(w))
+        T = w.L // 64
+        flops = 4.0 * 64 * 64 * w.D * T * (T + 1) / 2 * w.Z * w.H
+        pa = s2o.make_params(w.Z, w.H, w.Hkv, w.L, w.D, w.L, w.BM, w.BN, use_q_perm=0)
+        state = torch.empty(s2o.s2o_attention_sizes(pa)["scratch"], dtype=torch.uint8, device="cuda:0")
+        O = torch.empty_like(Qd)
+        cnt = torch.empty((w.Z, w.H, w.L // w.BM), dtype=torch.int32, device="cuda:0")
+        cnt2 = torch.empty_like(cnt)
+        kw = dict(O=O, computed=cnt, skipped=cnt2, scratch=state)
+        p2 = s2o.make_params(w.Z, w.H, w.Hkv, w.L, w.D, w.S, w.BM, w.BN, stop_mode=2)
+        p0 = s2o.make_params(w.Z, w.H, w.Hkv, w.L, w.D, w.S, w.BM, w.BN, stop_mode=0)
+        plan = s2o.s2o_plan(Qd, Kd, p2, want_scores=False)
+        N = w.L // w.S
+        qi = torch.arange(w.S, dtype=torch.int32, device="cuda:0").expand(w.Z, w.H, N, w.S).contiguous()
+        row = torch.cat([torch.arange(n * w.S, dtype=torch.int32, device="cuda:0") for n in range(1, N)])
+        ki = row.expand(w.Z, w.H, row.numel()).contiguous()
+        variants = [lambda: s2o.s2o_attention(Qd, Kd, Vd, pa, None, None, -1.0, **kw),
+                    lambda: s2o.s2o_attention(Qd, Kd, Vd, p2, qi, ki, -1.0, **kw),
+                    lambda: s2o.s2o_attention(Qd, Kd, Vd, p2, plan.q_perm, plan.kv_perm, -1.0, **kw),
+                    lambda: s2o.s2o_attention(Qd, Kd, Vd, p0, plan.q_perm, plan.kv_perm, -1.0, **kw)]
+        # the clock sags as the chip warms up: interleave the variants and take medians
+        times = [[] for _ in variants]
+        for rep in range(5):
+            for i, fn in enumerate(variants):
+                times[i].append(_timed(fn, 1))
+        a, b, c, d = (float(np.median(t)) for t in times)
+        print(f"| {w.L} | {w.S} | {a:.2f} ({flops / a / 1e9:.0f}) | {b:.2f} | {c:.2f} | {d:.2f} | "
+              f"{b / a:.3f} | {c / b:.3f} | {d / c:.3f} |", flush=True)
+        del Qd, Kd, Vd, O, state, plan, qi, ki
+        torch.cuda.empty_cache()
+
+
+def plan_table():
+    import torch
+    from . import binding as s2o, inputs
+    Ss = (512, 1024, 2048, 4096)
+    print("| L | " + " | ".join(f"S={S} ms (ms*S/L^2 *1e9)" for S in Ss) + " |")
+    print("|---|" + "---|" * len(Ss))
+    for L in (4096, 8192, 16384, 32768, 65536, 131072):
+        w = inputs.workload("llama128k", L=L, S=min(2048, L // 2))
+        Qb, Kb, _ = inputs.make_qkv(w)
+        Qd, Kd = _dev(Qb), _dev(Kb)
+        cells = []
+        for S in Ss:
+            if L // S < 2:
+                cells.append("-")
+                continue
+            p = s2o.make_params(w.Z, w.H, w.Hkv, L, w.D, S)
+            scratch = torch.empty(s2o.s2o_plan_sizes(p)["scratch"], dtype=torch.uint8, device="cuda:0")
+            N = L // S
+            P = S * N * (N - 1) // 2
+            maps = (torch.empty((w.Z, w.H, N, S), dtype=torch.int32, device="cuda:0"),
+                    torch.empty((w.Z, w.H, max(P, 4)), dtype=torch.int32, device="cuda:0"))
+            ms = _timed(lambda: s2o.s2o_plan(Qd, Kd, p, want_scores=False, scratch=scratch, maps=maps), 5)
+            cells.append(f"{ms:.3f} ({ms * S / L / L * 1e9:.1f})")
+            del scratch, maps
+        print(f"| {L} | " + " | ".join(cells) + " |", flush=True)
+        del Qd, Kd
+        torch.cuda.empty_cache()
+
+
+if __name__ == "__main__":
+    what = sys.argv[1] if len(sys.argv) > 1 else ""
+    if what == "abcd":
+        abcd()
+    elif what == "plan-table":
+        plan_table()
+    else:
+        print(__doc__)
+        sys.exit(2)
