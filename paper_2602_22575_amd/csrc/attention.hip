@@ -423,29 +423,29 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     ++it;
     for (; it < ntiles; ++it) {
       const int* vf = vote_flags(it - 1);
-      int any = 0;
+      int fl[kWaves];
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) any |= vf[w];
+      for (int w = 0; w < kWaves; ++w) fl[w] = vf[w];
       int votes = 0;
       for (int p2 = 0; p2 < wpt; ++p2) votes |= vf[tile_l + tpw * p2];
-      const bool stop = votes == 0;
-      if (stop && a.stop_mode == 0) {                  // the triggering tile is dropped
-        l_run = l_save; m_ref = m_save;
-        pending = false;
-        wg_done = any == 0;
-        break;
-      }
-      if (stop) {                                      // mode 1: fold it in, then stop
-        rescale(alpha_pend, grow_pend);
-        pv((it - 1) % 3, pb_pend);
-        ++committed;
+      qk(it & 1);
+      if (votes == 0) {
+        int any = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) any |= fl[w];
+        if (a.stop_mode == 0) {
+          l_run = l_save; m_ref = m_save;
+        } else {
+          rescale(alpha_pend, grow_pend);
+          pv((it - 1) % 3, pb_pend);
+          ++committed;
+        }
         pending = false;
         wg_done = any == 0;
         break;
       }
       if (it + 1 < ntiles) load_tile(it + 1);
       rescale(alpha_pend, grow_pend);
-      qk(it & 1);
       pv((it - 1) % 3, pb_pend);
       ++committed;
       softmax(std::false_type{}, it);
