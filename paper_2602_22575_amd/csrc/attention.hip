@@ -423,16 +423,13 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     ++it;
     for (; it < ntiles; ++it) {
       const int* vf = vote_flags(it - 1);
-      int fl[kWaves];
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) fl[w] = vf[w];
       int votes = 0;
       for (int p2 = 0; p2 < wpt; ++p2) votes |= vf[tile_l + tpw * p2];
       qk(it & 1);
       if (votes == 0) {
         int any = 0;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) any |= fl[w];
+        for (int w = 0; w < kWaves; ++w) any |= vf[w];
         if (a.stop_mode == 0) {
           l_run = l_save; m_ref = m_save;
         } else {
