@@ -194,6 +194,41 @@ def test_dense_contiguous_long_segment(gpu):
         assert np.abs(O[:, :, rows] - ref).max() <= parity.O_MAX_ABS
 
 
+def test_strided_token_major_layout_and_batch(gpu):
+    """Z = 2 and Q/K/V/O stored token-major ([Z, L, H, D], the layout most model code keeps)
+    described by element strides: maps and output must equal, bit for bit, those of the packed
+    [Z, H, L, D] run, which is itself checked against the oracle."""
+    import torch
+    import paper_2602_22575_amd as s2o
+    w = inputs.workload("llama8k", Z=2, L=1024, S=256, H=4, Hkv=2, seed=11)
+    _say("case: strided layout, Z=2")
+    Qb, Kb, Vb = inputs.make_qkv(w)
+    Qd, Kd, Vd = (gu.to_dev(x) for x in (Qb, Kb, Vb))
+    plan, pg = gu.gpu_plan(w, Qd, Kd)
+    parity.check_plan(w, Qb, Kb, pg)
+    tau = 0.03
+    Ob, c, sk = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau)
+    parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, 0, Ob, c, sk)
+    # token-major storage
+    Qt, Kt, Vt = (x.permute(0, 2, 1, 3).contiguous() for x in (Qd, Kd, Vd))
+    D, L, H, Hkv = w.D, w.L, w.H, w.Hkv
+    qs, ks = (L * H * D, D, H * D), (L * Hkv * D, D, Hkv * D)
+    p = s2o.make_params(w.Z, H, Hkv, L, D, w.S, w.BM, w.BN, q_stride=qs, k_stride=ks, v_stride=ks, o_stride=qs)
+    plan2 = s2o.s2o_plan(Qt, Kt, p, want_scores=True)
+    Ot = torch.zeros((w.Z, L, H, D), dtype=torch.bfloat16, device="cuda:0")
+    for two_pass in (True, False):
+        _, c2, s2_ = s2o.s2o_attention(Qt, Kt, Vt, p, plan2.q_perm, plan2.kv_perm, tau, O=Ot, two_pass=two_pass)
+        torch.cuda.synchronize()
+        assert torch.equal(plan2.q_perm, plan.q_perm) and torch.equal(plan2.kv_perm, plan.kv_perm)
+        assert torch.equal(plan2.s_k, plan.s_k) and torch.equal(plan2.s_q, plan.s_q)
+        assert np.array_equal(c2.cpu().numpy(), c) and np.array_equal(s2_.cpu().numpy(), sk)
+        got = gu.bits_of(Ot.permute(0, 2, 1, 3).contiguous())
+        if two_pass:
+            assert np.array_equal(got, Ob)
+        else:
+            assert np.abs(parity.to_f64(got) - parity.to_f64(Ob)).max() <= parity.O_MAX_ABS
+
+
 def test_separate_passes_equal_the_combined_call(tiny):
     """s2o_attention_local + s2o_attention_prefix (the local pass issued before the plan, as a
     caller overlapping the two would) give bit-identical results to s2o_attention with a
