@@ -50,7 +50,7 @@ constexpr int kD = 128;
 constexpr int kNBMax = 64;         // buckets per prefix row (upper bound)
 constexpr int kBucketAvg = 2048;   // target average bucket population
 constexpr int kSampleStride = 64;  // one sampled score per this many tokens
-constexpr int kSplStride = kNBMax + 1;   // floats per row of splitters in LDS (odd: no bank pile-up)
+constexpr int kSplStride = kNBMax + 4;   // floats per row of splitters in LDS (rows 16-byte aligned)
 constexpr int kSpanCap = 4096;     // elements one span_sort workgroup sorts in LDS
 constexpr int kSubBuckets = 2048;  // fine buckets of the in-LDS sort
 constexpr int kSubMax = 64;        // a fuller sub-bucket sends the span to the bitonic fallback
@@ -335,6 +335,26 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
     }
   }
   const float* myspl = spl + m_ * kSplStride;
+  // Bucket of a score = number of the row's (descending) splitters above it.  Two levels,
+  // both by counting instead of a dependent binary search: every 8th splitter sits in a
+  // register, the group of 7 below the hit comes from LDS with two independent 16-byte reads.
+  float top[7];
+  if (MODE != 0) {
+    __syncthreads();                         // the rows written above are read by other lanes
+#pragma unroll
+    for (int k = 0; k < 7; ++k) top[k] = myspl[8 * k + 7];
+  }
+  auto bucket_of = [&](float sv) {
+    int gi = 0;
+#pragma unroll
+    for (int k = 0; k < 7; ++k) gi += top[k] > sv ? 1 : 0;
+    const f32x4 lo = *reinterpret_cast<const f32x4*>(myspl + 8 * gi);
+    const f32x4 hi = *reinterpret_cast<const f32x4*>(myspl + 8 * gi + 4);
+    int bk = 8 * gi;
+    bk += lo[0] > sv ? 1 : 0; bk += lo[1] > sv ? 1 : 0; bk += lo[2] > sv ? 1 : 0; bk += lo[3] > sv ? 1 : 0;
+    bk += hi[0] > sv ? 1 : 0; bk += hi[1] > sv ? 1 : 0; bk += hi[2] > sv ? 1 : 0;
+    return bk;
+  };
   const int samples_per_row = a.L / kSampleStride;
 
   // K tile loader: thread (c, q) moves 16-byte chunk c of rows q, q+16, ...
@@ -389,32 +409,37 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
             sc.samples[row_id * samples_per_row + blk] = v;
           }
         }
-        // the four registers of a group are four consecutive tokens
+        // the four registers of a group are four consecutive tokens; lim is a multiple of
+        // 64, so a 32-token block is valid for this row as a whole or not at all
+        if (t0 + 32 * sb < lim) {
+          if (MODE == 0) {
+            if (a.s_k) {
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const int t = t0 + 32 * sb + 8 * i4 + 4 * hh;
-          if (t < lim) {                   // lim is a multiple of 64: all four or none
-            if (MODE == 0) {
-              if (a.s_k) {
+              for (int i4 = 0; i4 < 4; ++i4) {
+                const int t = t0 + 32 * sb + 8 * i4 + 4 * hh;
                 const f32x4 v = {acc[4 * i4], acc[4 * i4 + 1], acc[4 * i4 + 2], acc[4 * i4 + 3]};
                 *reinterpret_cast<f32x4*>(a.s_k + base + t) = v;
               }
+            }
+          } else {
+            // all sixteen bucket searches first (independent LDS reads), then the counter
+            // updates: interleaved, every search would wait behind the previous key's atomic
+            int bk[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) bk[i] = bucket_of(acc[i]);
+            if (MODE == 1) {
+#pragma unroll
+              for (int i = 0; i < 16; ++i)
+                atomicAdd(&hist[m_ * kCntWords + (bk[i] >> 1)], 1u << (16 * (bk[i] & 1)));
             } else {
+              uint32_t pos[16];
 #pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const float sv = acc[4 * i4 + e];
-                // bucket = number of splitters above the score (descending splitters)
-                int bk = 0;
+              for (int i = 0; i < 16; ++i) pos[i] = atomicAdd(&hist[m_ * kCntWords + bk[i]], 1u);
 #pragma unroll
-                for (int step = kNBMax / 2; step > 0; step >>= 1)
-                  bk += myspl[bk + step - 1] > sv ? step : 0;
-                if (MODE == 1) {
-                  atomicAdd(&hist[m_ * kCntWords + (bk >> 1)], 1u << (16 * (bk & 1)));
-                } else {
-                  const uint32_t pos = atomicAdd(&hist[m_ * kCntWords + bk], 1u);
-                  if (pos < (uint32_t)lim) sc.pairs[base + pos] = sort_key(sv, (uint32_t)(t + e));
-                  else sc.counters[2] = 1u;
-                }
+              for (int i = 0; i < 16; ++i) {
+                const int t = t0 + 32 * sb + 8 * (i >> 2) + 4 * hh + (i & 3);
+                if (pos[i] < (uint32_t)lim) sc.pairs[base + pos[i]] = sort_key(acc[i], (uint32_t)t);
+                else sc.counters[2] = 1u;
               }
             }
           }
