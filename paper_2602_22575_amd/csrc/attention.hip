@@ -242,7 +242,10 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   const float c2 = a.scale_log2e;
   // state buffers: row (z, h, l) -> acc [128] fp32 in the accumulator's register order, l, m
   const int64_t st_row = zh * a.L + nS + qoff;
-  if (PASS == 2 && active) {
+  // The statistics are needed by the first softmax; the accumulator only by the first PV
+  // product, which in the prefix walk runs one step late: its 512 bytes per row are
+  // requested after the first tile's scores have been issued and arrive behind them.
+  auto load_acc = [&] {
     const float* sp = a.st_acc + st_row * kD + 64 * hh;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -251,6 +254,9 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
         const f32x4 v = *reinterpret_cast<const f32x4*>(sp + 16 * db + 4 * i4);
         o[db][4 * i4] = v[0]; o[db][4 * i4 + 1] = v[1]; o[db][4 * i4 + 2] = v[2]; o[db][4 * i4 + 3] = v[3];
       }
+  };
+  bool acc_loaded = PASS != 2;
+  if (PASS == 2 && active) {
     l_run = a.st_l[st_row];
     m_ref = a.st_m[st_row];
   }
@@ -382,6 +388,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
       else softmax(std::true_type{}, it);
       bf16x8 pb[4];
       pack_p(pb);
+      if (!acc_loaded) { load_acc(); acc_loaded = true; }
       rescale(alpha, grow);
       pv(it % 3, pb);
       l_run = prev + mass;
@@ -417,6 +424,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     // first prefix tile: scores only
     if (it + 1 < ntiles) load_tile(it + 1);
     qk(it & 1);
+    if (!acc_loaded) { load_acc(); acc_loaded = true; }
     softmax(std::false_type{}, it);
     publish(it);
     __syncthreads();
@@ -481,6 +489,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   }
 
   if (j < TJ) {
+    if (!acc_loaded) load_acc();                 // no prefix tile was walked (first segment)
     if (PASS == 1) {
       // leave the un-normalised state for the second pass
       float* sp = a.st_acc + st_row * kD + 64 * hh;
