@@ -187,19 +187,26 @@ def main():
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
-    # per-stage device time, each stage alone, with events on the stream it is launched on
-    reps = max(args.steps, 3)
-    plan_ms = float(np.mean(timed(do_plan, reps)))
+    # per-stage device time, each stage alone, with events on the stream it is launched on:
+    # 5 warm-up + 20 timed launches each, median reported (mean beside it)
+    def stage(fn, reps=20, warm=5):
+        for _ in range(warm):
+            fn()
+        t = timed(fn, reps)
+        return float(np.median(t)), float(np.mean(t))
+
+    plan_ms, plan_mean = stage(do_plan)
     if args.fused:
         attn_fn = lambda tau, out=O: s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau, O=out,
                                                        computed=comp, skipped=skip, two_pass=False)
-        local_ms = None
-        attn_ms = prefix_ms = float(np.mean(timed(lambda: attn_fn(args.tau), reps)))
+        local_ms = local_mean = None
+        prefix_ms, prefix_mean = stage(lambda: attn_fn(args.tau))
+        attn_ms = prefix_ms
     else:
-        local_ms = float(np.mean(timed(lambda: s2o.s2o_attention_local(Qd, Kd, Vd, params, scratch=state), reps)))
+        local_ms, local_mean = stage(lambda: s2o.s2o_attention_local(Qd, Kd, Vd, params, scratch=state))
         attn_fn = lambda tau, out=O: s2o.s2o_attention_prefix(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau,
                                                               state, O=out, computed=comp, skipped=skip)
-        prefix_ms = float(np.mean(timed(lambda: attn_fn(args.tau), reps)))
+        prefix_ms, prefix_mean = stage(lambda: attn_fn(args.tau))
         attn_ms = local_ms + prefix_ms
     c, s = comp.cpu().numpy(), skip.cpu().numpy()
     flops, trig = tile_flops(w, c, s)
@@ -246,6 +253,7 @@ def main():
         "config": {"workload": f"{w.name}: Z={w.Z} H={w.H} Hkv={w.Hkv} L={w.L} D={w.D} S={w.S} "
                                f"tiles {w.BM}x{w.BN} tau={args.tau} stop_mode=0 seed={w.seed}"},
         "plan_ms": plan_ms, "attn_ms": attn_ms, "attn_local_ms": local_ms, "attn_prefix_ms": prefix_ms,
+        "stage_means_ms": {"plan": plan_mean, "attn_local": local_mean, "attn_prefix": prefix_mean},
         "attn_local_tflops": None if local_ms is None else local_flops / (local_ms * 1e-3) / 1e12,
         "streams": 1 if side_stream is None else 2, "density": dens, "sparsity": 1 - dens,
         "tflops_on_computed_blocks": tflops, "triggering_tiles": trig,
@@ -294,10 +302,20 @@ def cpu_baseline(w, Qb, Kb, Vb, plan, tau, issued_tiles_gpu):
             tiles += int((n * (w.S // w.BN) - s[0, 0, n * tj:(n + 1) * tj]).sum()) + orc.pass1_tiles(w.S, w.S, w.BM)
     dt = time.perf_counter() - t0
     total_tiles = issued_tiles_gpu + orc.pass1_tiles(w.L, w.S, w.BM) * w.Z * w.H
-    return {"value": dt / max(tiles, 1) * total_tiles * 1e3, "unit": "ms/layer (extrapolated from the sample)",
-            "cores": int(cores), "kind": "oracle",
+    attn_ms = dt / max(tiles, 1) * total_tiles * 1e3
+    # Alg. 1 on two query heads (all segments), scaled to all heads
+    ph = sorted({0, w.H - 1})
+    t0 = time.perf_counter()
+    for h in ph:
+        g = h // G
+        orc.plan(orc.bf16_bits_to_f64(Qb[:, h:h + 1]), orc.bf16_bits_to_f64(Kb[:, g:g + 1]), w.S)
+    dp = time.perf_counter() - t0
+    plan_ms = dp / len(ph) * w.H * 1e3
+    return {"value": attn_ms + plan_ms, "unit": "ms/layer (extrapolated from the sample)",
+            "cores": int(cores), "kind": "oracle", "plan_ms": plan_ms, "attn_ms": attn_ms,
             "sample": f"oracle attention (Alg. 2+3, fp64 numpy) on heads {heads} x segments {segs}: "
-                      f"{tiles} tiles in {dt:.1f} s, scaled by issued tiles to the full layer; plan excluded"}
+                      f"{tiles} tiles in {dt:.1f} s, scaled by issued tiles to the full layer; oracle plan "
+                      f"(Alg. 1) on heads {ph}: {dp:.1f} s, scaled by heads"}
 
 
 if __name__ == "__main__":

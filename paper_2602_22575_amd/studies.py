@@ -12,6 +12,10 @@
       retrieval-latency table in "Additional details on end-to-end operator performance"),
       with time * S / L^2 to check the L^2 / S law.
 
+  python -m paper_2602_22575_amd.studies mixed        the mixed workload (half the KV groups
+      unstructured, half with a strong heavy-key boost) at 64x64 and 128x64 tiles: times and
+      the spread of the per-head density.
+
 Inputs are the seeded synthetic workloads of inputs.py; every figure is the mean of a few
 launches timed with events on the launch stream.
 """
@@ -108,12 +112,47 @@ def plan_table():
         torch.cuda.empty_cache()
 
 
+def mixed():
+    import torch
+    from . import binding as s2o, inputs
+    w0 = inputs.workload("mixed128k")
+    Qd, Kd, Vd = (_dev(x) for x in inputs.make_qkv(w0))
+    tau = 5e-3
+    print(f"workload {w0.name}: L={w0.L} S={w0.S} tau={tau}; heads 0-{w0.H // 2 - 1} unstructured, the rest boosted")
+    print("| tiles | local ms | prefix ms | density all heads | unstructured heads min/median/max | boosted heads min/median/max |")
+    print("|---|---|---|---|---|---|")
+    for BM in (64, 128):
+        p = s2o.make_params(w0.Z, w0.H, w0.Hkv, w0.L, w0.D, w0.S, BM, w0.BN)
+        plan = s2o.s2o_plan(Qd, Kd, p, want_scores=False)
+        state = torch.empty(s2o.s2o_attention_sizes(p)["scratch"], dtype=torch.uint8, device="cuda:0")
+        O = torch.empty_like(Qd)
+        c = torch.empty((w0.Z, w0.H, w0.L // BM), dtype=torch.int32, device="cuda:0")
+        sk = torch.empty_like(c)
+        tl = _timed(lambda: s2o.s2o_attention_local(Qd, Kd, Vd, p, scratch=state), 5)
+        tp = _timed(lambda: s2o.s2o_attention_prefix(Qd, Kd, Vd, p, plan.q_perm, plan.kv_perm, tau, state, O=O,
+                                                     computed=c, skipped=sk), 5)
+        skn = sk.cpu().numpy()[0]                                   # [H, L/BM]
+        N, TJ, per = w0.L // w0.S, w0.S // BM, w0.S // w0.BN
+        nk = np.repeat(np.arange(N) * per, TJ)
+        local = N * sum(-(-((b + 1) * BM) // w0.BN) for b in range(TJ))
+        causal = sum(-(-((b + 1) * BM) // w0.BN) for b in range(w0.L // BM))
+        dens = (local + (nk[None] - skn).sum(axis=1)) / causal      # per head
+        half = w0.H // 2
+        fmt = lambda d: f"{d.min():.4f} / {np.median(d):.4f} / {d.max():.4f}"
+        print(f"| {BM}x{w0.BN} | {tl:.2f} | {tp:.2f} | {dens.mean():.4f} | {fmt(dens[:half])} | {fmt(dens[half:])} |",
+              flush=True)
+        del plan, state, O, c, sk
+        torch.cuda.empty_cache()
+
+
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else ""
     if what == "abcd":
         abcd()
     elif what == "plan-table":
         plan_table()
+    elif what == "mixed":
+        mixed()
     else:
         print(__doc__)
         sys.exit(2)
