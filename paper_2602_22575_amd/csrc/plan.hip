@@ -14,7 +14,7 @@
 //                        any score distribution.  The kernel runs three times with different
 //                        epilogues:
 //                          MODE 0  one sampled score per 64 tokens (+ optional s_K store)
-//                          MODE 1  per (row, 1024-token chunk) bucket counts, kept in LDS
+//                          MODE 1  per (row, chunk of up to 1024 tokens) bucket counts, kept in LDS
 //                                  and written once per chunk (no global atomics)
 //                          MODE 2  scatter of (key, token) pairs to their bucket: global
 //                                  offset of the (row, chunk, bucket) cell + a rank taken
@@ -54,7 +54,7 @@ constexpr int kSplStride = kNBMax + 4;   // floats per row of splitters in LDS (
 constexpr int kSpanCap = 4096;     // elements one span_sort workgroup sorts in LDS
 constexpr int kSubBuckets = 2048;  // fine buckets of the in-LDS sort
 constexpr int kSubMax = 64;        // a fuller sub-bucket sends the span to the bitonic fallback
-constexpr int kChunk = 1024;       // key tokens per score workgroup
+constexpr int kChunkMax = 1024;    // key tokens per score workgroup (halved while the grid is too small)
 constexpr int kSub = 64;           // key tokens per LDS tile of the score kernel (32 in the scatter pass)
 constexpr int kKStride = 136;      // bf16 elements per K row in LDS (272 B)
 constexpr int kBigGrid = 64;       // workgroups of the fallback sort
@@ -87,7 +87,7 @@ struct Scratch {
   uint16_t* qsplit;   // [Z*H*N][3][128] bf16
   float* samples;     // [Z*H*N][L/64] one score per 64 tokens of the row's prefix
   float* splitters;   // [Z*H*N][kNBMax] descending; entries past the row's buckets are -inf
-  uint16_t* chist;    // [Z*H*N][maxch][kNBMax] bucket counts per 1024-token chunk
+  uint16_t* chist;    // [Z*H*N][maxch][kNBMax] bucket counts per chunk of `chunk` tokens
   uint32_t* coffs;    // same shape: offset of the cell inside its row
   uint32_t* counters; // [0]=#spans [1]=#big spans [2]=error flag
   int4* spans;        // [max_spans]  (row, begin, end, 0)
@@ -96,6 +96,7 @@ struct Scratch {
   uint64_t* alt;      // [kBigGrid * L]
   int64_t max_spans;
   int maxch;
+  int chunk;          // key tokens per score workgroup: kChunkMax, less for short sequences
   size_t total;
 };
 
@@ -107,7 +108,13 @@ static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S) {
   const int64_t P = kv_row_offset(N, S);
   Scratch s;
   s.max_spans = (int64_t)Z * H * (3 * P / kSpanCap + 2 * N) + 8;
-  s.maxch = (L + kChunk - 1) / kChunk;
+  // one workgroup per (KV head, 128 rows, chunk): keep at least ~1024 of them in the grid
+  {
+    const int64_t rbg = ((int64_t)(H / Hkv) * N + 127) / 128;
+    s.chunk = kChunkMax;
+    while (s.chunk > kSub && (int64_t)Z * Hkv * rbg * ((L + s.chunk - 1) / s.chunk) < 1024) s.chunk /= 2;
+  }
+  s.maxch = (L + s.chunk - 1) / s.chunk;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return (char*)base + o; };
   s.kguide = (float*)take((size_t)Z * Hkv * kD * 4);
@@ -247,7 +254,7 @@ __global__ __launch_bounds__(256) void pool_sq_sort_kernel(PlanArgs a, Scratch s
 }
 
 // ---------------------------------------------------------------------------------------
-// s_K scoring.  Workgroup = (z, g, group of 4 row blocks, chunk of kChunk tokens); wavefront w
+// s_K scoring.  Workgroup = (z, g, group of 4 row blocks, chunk of sc.chunk tokens); wavefront w
 // owns row block 4*group + w (32 rows of the contraction's N side) and keeps its q_mean split
 // fragments in registers for the whole chunk; the chunk's K rows pass through LDS in tiles
 // of kSub tokens shared by the four wavefronts.  Row r of KV head g is (hq = r / N,
@@ -270,7 +277,7 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
 
   const int G = a.H / a.Hkv;
   const int R = G * a.N;
-  const int nchunks = (a.L + kChunk - 1) / kChunk;
+  const int nchunks = (a.L + sc.chunk - 1) / sc.chunk;
   // all work on one KV head goes to one XCD (block ids are dealt round-robin to the 8 XCDs):
   // the scatter pass appends to ~R*kNBMax open cache lines per head, which fit one L2
   int unit, rest;
@@ -297,9 +304,9 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
   int lim_wg = 0, lim_wave = 0;
   for (int i = 0; i < 128; ++i) lim_wg = max(lim_wg, row_limit(128 * rbg + i));
   for (int i = 0; i < 32; ++i) lim_wave = max(lim_wave, row_limit(32 * rb + i));
-  const int t_begin = chunk * kChunk;
+  const int t_begin = chunk * sc.chunk;
   if (t_begin >= lim_wg) return;
-  const int t_end = min(t_begin + kChunk, lim_wg);
+  const int t_end = min(t_begin + sc.chunk, lim_wg);
 
   // this lane's row
   const int r = 32 * rb + m_;
@@ -501,7 +508,7 @@ __global__ __launch_bounds__(4 * kNBMax) void scan_kernel(PlanArgs a, Scratch sc
   if (n == 0) return;
   const int b = threadIdx.x % kNBMax, q = threadIdx.x / kNBMax;
   const int nb = row_buckets(n, a.S);
-  const int nch = (n * a.S + kChunk - 1) / kChunk;
+  const int nch = (n * a.S + sc.chunk - 1) / sc.chunk;
   const int c0 = (nch * q) / 4, c1 = (nch * (q + 1)) / 4;   // this thread's chunk range
   const uint16_t* ch = sc.chist + row_id * sc.maxch * kNBMax;
   uint32_t* co = sc.coffs + row_id * sc.maxch * kNBMax;
@@ -736,7 +743,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
   if (a.N > 1) {
     const int RB = (G * a.N + 31) / 32;
     const int RBG = (RB + 3) / 4;
-    const int nchunks = (a.L + kChunk - 1) / kChunk;
+    const int nchunks = sc.maxch;
     const dim3 grid((unsigned)((int64_t)a.Z * a.Hkv * RBG * nchunks));
     const size_t lds = (size_t)kSub * kKStride * 2 + 4 * 32 * (kNBMax / 2) * 4 + 4 * 32 * kSplStride * 4;
     const size_t lds2 = (size_t)32 * kKStride * 2 + 4 * 32 * kNBMax * 4 + 4 * 32 * kSplStride * 4;
