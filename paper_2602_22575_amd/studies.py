@@ -16,6 +16,10 @@
       unstructured, half with a strong heavy-key boost) at 64x64 and 128x64 tiles: times and
       the spread of the per-head density.
 
+  python -m paper_2602_22575_amd.studies qperm        with and without the query permutation
+      (paper's component ablation and "Single-pass Variant"): time, density and MSE against
+      the dense output, for the two-launch form, the fused launch, and original query order.
+
 Inputs are the seeded synthetic workloads of inputs.py; every figure is the mean of a few
 launches timed with events on the launch stream.
 """
@@ -112,6 +116,46 @@ def plan_table():
         torch.cuda.empty_cache()
 
 
+def qperm():
+    import torch
+    from . import binding as s2o, inputs
+    w = inputs.workload("llama128k")
+    Qd, Kd, Vd = (_dev(x) for x in inputs.make_qkv(w))
+    p1 = s2o.make_params(w.Z, w.H, w.Hkv, w.L, w.D, w.S, w.BM, w.BN, use_q_perm=1)
+    p0 = s2o.make_params(w.Z, w.H, w.Hkv, w.L, w.D, w.S, w.BM, w.BN, use_q_perm=0)
+    plan = s2o.s2o_plan(Qd, Kd, p1, want_scores=False)
+    state = torch.empty(s2o.s2o_attention_sizes(p1)["scratch"], dtype=torch.uint8, device="cuda:0")
+    dense = torch.empty_like(Qd)
+    s2o.s2o_attention(Qd, Kd, Vd, p1, plan.q_perm, plan.kv_perm, 0.0, O=dense, scratch=state)
+    ref = dense.float()
+    den2 = float((ref ** 2).sum())
+    N, TJ, per = w.L // w.S, w.S // w.BM, w.S // w.BN
+    nk = torch.from_numpy(np.repeat(np.arange(N) * per, TJ)).to("cuda:0")
+    T = w.L // w.BM
+    causal = T * (T + 1) // 2
+    local = N * TJ * (TJ + 1) // 2
+    O = torch.empty_like(Qd)
+    c = torch.empty((w.Z, w.H, w.L // w.BM), dtype=torch.int32, device="cuda:0")
+    sk = torch.empty_like(c)
+    print(f"workload {w.name}: L={w.L} S={w.S}, 64x64 tiles")
+    print("| tau | variant | attention ms | density | MSE vs dense | relative MSE |")
+    print("|---|---|---|---|---|---|")
+    for tau in (1e-3, 5e-3, 2e-2):
+        variants = [("Q_perm, two launches (Alg. 2 + Alg. 3)", p1, plan.q_perm, True),
+                    ("Q_perm, one fused launch", p1, plan.q_perm, False),
+                    ("original query order, one fused launch (Alg. 4)", p0, None, False),
+                    ("original query order, two launches", p0, None, True)]
+        for name, p, qp, two in variants:
+            fn = lambda: s2o.s2o_attention(Qd, Kd, Vd, p, qp, plan.kv_perm, tau, O=O, computed=c, skipped=sk,
+                                           scratch=state if two else None, two_pass=two)
+            ms = _timed(fn, 3)
+            dens = float((local * w.H + (nk[None, None] - sk).sum()) / (causal * w.H))
+            d = O.float() - ref
+            mse = float((d ** 2).mean(dim=(0, 2, 3)).mean())
+            print(f"| {tau} | {name} | {ms:.2f} | {dens:.4f} | {mse:.3e} | {float((d ** 2).sum()) / den2:.3e} |", flush=True)
+            del d
+
+
 def mixed():
     import torch
     from . import binding as s2o, inputs
@@ -153,6 +197,8 @@ if __name__ == "__main__":
         plan_table()
     elif what == "mixed":
         mixed()
+    elif what == "qperm":
+        qperm()
     else:
         print(__doc__)
         sys.exit(2)
