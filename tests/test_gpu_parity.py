@@ -327,7 +327,7 @@ def test_llama8k(gpu):
                 assert err.max() <= parity.O_MAX_ABS
 
 
-def _sampled_case(name, plan_heads, attn_samples, taus, stop_mode=0, **overrides):
+def _sampled_case(name, plan_heads, attn_samples, taus, stop_mode=0, variants=(), **overrides):
     """Full-size workload in the launch configuration bench.py times (all heads, whole
     sequence on the GPU); the oracle checks the plan on a few heads and the attention on a
     few (head, segment) pairs it can compute one by one."""
@@ -359,11 +359,23 @@ def _sampled_case(name, plan_heads, attn_samples, taus, stop_mode=0, **overrides
             st.pop("gains")
             _say(f"   head {h} segments {segs}:", st)
         _say("   mean density", float(orc.density(s, w.L, w.S, w.BM, w.BN).mean()))
+    # further launch forms at the first threshold: (stop_mode, two launches?, tile budget)
+    for sm, two_pass, budget in variants:
+        tau = taus[0]
+        _say(f"case: {name} attention tau={tau} stop_mode={sm} two_pass={two_pass} budget={budget}")
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, sm, two_pass=two_pass,
+                                    max_tiles=budget)
+        for h, segs in attn_samples:
+            st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, sm, Ob, c, s,
+                                        heads=[h], segments=segs, max_tiles=budget)
+            st.pop("gains", None)
+            _say(f"   head {h} segments {segs}:", st)
 
 
 def test_llama32k_sampled(gpu):
     """32K, heavy tokens in bursts (token-level non-contiguous gather), tau = 1e-3."""
-    _sampled_case("llama32k", plan_heads=[0, 9, 18, 27], attn_samples=[(0, [1, 8, 15]), (27, [5])], taus=(1e-3,))
+    _sampled_case("llama32k", plan_heads=[0, 9, 18, 27], attn_samples=[(0, [1, 8, 15]), (27, [5])], taus=(1e-3,),
+                  variants=[(1, True, 0), (0, False, 0), (0, True, 40), (2, True, 25)])
 
 
 def test_llama128k_sampled(gpu):
