@@ -528,17 +528,19 @@ size_t attention_state_bytes(int Z, int H, int L) {
 }
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
-  static bool attr_set = false;
-  if (!attr_set) {
+  static std::mutex mu;
+  static uint64_t done = 0;
+  const hipError_t se = once_per_device(mu, done, [] {
     const void* fns[3] = {reinterpret_cast<const void*>(&s2o_attention_kernel<0>),
                           reinterpret_cast<const void*>(&s2o_attention_kernel<1>),
                           reinterpret_cast<const void*>(&s2o_attention_kernel<2>)};
     for (const void* f : fns) {
-      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds);
+      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds);
       if (e != hipSuccess) return e;
     }
-    attr_set = true;
-  }
+    return hipSuccess;
+  });
+  if (se != hipSuccess) return se;
   const int TJ = a.S / a.BM;
   const int tpw = kWaves / (a.BM / kRowsPerWave);
   const int JG = (TJ + tpw - 1) / tpw;

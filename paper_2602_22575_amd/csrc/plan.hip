@@ -724,6 +724,28 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
   if (sc.total > a.scratch_bytes) return hipErrorInvalidValue;
   const int64_t rows = (int64_t)a.Z * a.H * a.N;
   const int G = a.H / a.Hkv;
+  // dynamic LDS limits of the kernels that need more than the default
+  constexpr size_t kScoreLds = (size_t)kSub * kKStride * 2 + 4 * 32 * (kNBMax / 2) * 4 + 4 * 32 * kSplStride * 4;
+  constexpr size_t kScatterLds = (size_t)32 * kKStride * 2 + 4 * 32 * kNBMax * 4 + 4 * 32 * kSplStride * 4;
+  constexpr size_t kSplitterLdsMax = 128 * 1024;   // a row's sample (L / 64 scores, 8-byte keys) is sorted in LDS
+  {
+    static std::mutex mu;
+    static uint64_t done = 0;
+    const hipError_t se = once_per_device(mu, done, [] {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pool_sq_sort_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8 + 16 * kD * 4);
+      if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<0>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScoreLds);
+      if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<1>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScoreLds);
+      if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<2>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScatterLds);
+      if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&splitter_kernel),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSplitterLdsMax);
+      return e;
+    });
+    if (se != hipSuccess) return se;
+  }
 
   hipLaunchKernelGGL(init_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream, sc, rows);
   hipLaunchKernelGGL(kguide_kernel, dim3(a.Z * a.Hkv), dim3(256), 0, stream, a, sc);
@@ -731,13 +753,6 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
     int n2 = 1;
     while (n2 < a.S) n2 <<= 1;
     const size_t lds = (size_t)n2 * 8 + 16 * kD * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pool_sq_sort_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8 + 16 * kD * 4);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
     hipLaunchKernelGGL(pool_sq_sort_kernel, dim3((unsigned)rows), dim3(256), lds, stream, a, sc);
   }
   if (a.N > 1) {
@@ -745,23 +760,12 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
     const int RBG = (RB + 3) / 4;
     const int nchunks = sc.maxch;
     const dim3 grid((unsigned)((int64_t)a.Z * a.Hkv * RBG * nchunks));
-    const size_t lds = (size_t)kSub * kKStride * 2 + 4 * 32 * (kNBMax / 2) * 4 + 4 * 32 * kSplStride * 4;
-    const size_t lds2 = (size_t)32 * kKStride * 2 + 4 * 32 * kNBMax * 4 + 4 * 32 * kSplStride * 4;
-    static bool attr2_set = false;
-    if (!attr2_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<0>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<1>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<2>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
-      if (e != hipSuccess) return e;
-      attr2_set = true;
-    }
+    const size_t lds = kScoreLds, lds2 = kScatterLds;
     hipLaunchKernelGGL(score_kernel<0>, grid, dim3(256), lds, stream, a, sc);
     {
       int ns2 = 1;
       while (ns2 < a.L / kSampleStride) ns2 <<= 1;
+      if ((size_t)ns2 * 8 > kSplitterLdsMax) return hipErrorInvalidValue;   // L > 1M tokens
       hipLaunchKernelGGL(splitter_kernel, dim3((unsigned)rows), dim3(256), (size_t)ns2 * 8, stream, a, sc);
     }
     hipLaunchKernelGGL(score_kernel<1>, grid, dim3(256), lds, stream, a, sc);

@@ -3,10 +3,28 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 namespace s2o {
 
 // Packed start of prefix row n (n >= 1) inside one head's KV_perm / s_K array.
 __host__ __device__ inline int64_t kv_row_offset(int64_t n, int64_t S) { return S * n * (n - 1) / 2; }
+
+// Runs `setup` (kernel attributes such as the dynamic LDS limit are per device) once per
+// device, before the first launch there; other host threads wait until it is done.  A failed
+// setup is retried by the next call.
+template <class F>
+inline hipError_t once_per_device(std::mutex& mu, uint64_t& done, F setup) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  std::lock_guard<std::mutex> lock(mu);
+  if (done & bit) return hipSuccess;
+  e = setup();
+  if (e == hipSuccess) done |= bit;
+  return e;
+}
 
 struct AttnArgs {
   const uint16_t* Q;
