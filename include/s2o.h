@@ -18,7 +18,10 @@
  *   - The library never allocates or frees device memory and never synchronises: a call
  *     validates its arguments on the host, enqueues kernels on `stream` (a hipStream_t
  *     passed as void*, NULL = the default stream) and returns.  The caller owns all
- *     buffers and keeps them alive until the stream has passed the call.
+ *     buffers and keeps them alive until the stream has passed the call.  Because a call
+ *     only enqueues kernels (no memset or copy nodes), it can be recorded into a HIP graph
+ *     once it has run one time on the device outside a capture (the first call on a device
+ *     sets kernel attributes).
  *   - Return value: S2O_OK (0) or a negative code.  On an argument error nothing is
  *     enqueued and nothing is written.
  *   - Tensors: Q [Z,H,L,D], K and V [Z,Hkv,L,D], O [Z,H,L,D]; bf16; the last dimension is

@@ -229,6 +229,66 @@ def test_strided_token_major_layout_and_batch(gpu):
             assert np.abs(parity.to_f64(got) - parity.to_f64(Ob)).max() <= parity.O_MAX_ABS
 
 
+def test_graph_capture_and_replay(gpu):
+    """The library only enqueues kernels on the caller's stream (no allocation, no host
+    synchronisation, no memset nodes), so plan + attention can be captured in a HIP graph.
+    Replays on changed inputs, with eager work and synchronisations in between, must give
+    exactly what eager calls give on the same inputs."""
+    import torch
+    import paper_2602_22575_amd as s2o
+    w = inputs.workload("llama8k", L=2048, S=256, H=4, Hkv=2, seed=21)
+    _say("case: graph capture, L=2048")
+    p = gu.params_for(w)
+    sets = []
+    for seed in (21, 22, 23):
+        Qb, Kb, Vb = inputs.make_qkv(inputs.workload("llama8k", L=2048, S=256, H=4, Hkv=2, seed=seed))
+        sets.append([gu.to_dev(x) for x in (Qb, Kb, Vb)])
+    N = w.L // w.S
+    P = w.S * N * (N - 1) // 2
+    dev = "cuda:0"
+    Qs, Ks, Vs = (torch.empty_like(x) for x in sets[0])              # static graph inputs
+    maps = (torch.empty((w.Z, w.H, N, w.S), dtype=torch.int32, device=dev),
+            torch.empty((w.Z, w.H, P), dtype=torch.int32, device=dev))
+    pscr = torch.empty(s2o.s2o_plan_sizes(p)["scratch"], dtype=torch.uint8, device=dev)
+    ascr = torch.empty(s2o.s2o_attention_sizes(p)["scratch"], dtype=torch.uint8, device=dev)
+    O = torch.empty_like(Qs)
+    c = torch.empty((w.Z, w.H, w.L // w.BM), dtype=torch.int32, device=dev)
+    sk = torch.empty_like(c)
+    tau = 0.03
+
+    def run():
+        plan = s2o.s2o_plan(Qs, Ks, p, want_scores=False, scratch=pscr, maps=maps)
+        s2o.s2o_attention(Qs, Ks, Vs, p, plan.q_perm, plan.kv_perm, tau, O=O, computed=c, skipped=sk, scratch=ascr)
+
+    def eager(Q, K, V):
+        plan = s2o.s2o_plan(Q, K, p, want_scores=False)
+        out = s2o.s2o_attention(Q, K, V, p, plan.q_perm, plan.kv_perm, tau)
+        torch.cuda.synchronize()
+        return plan.q_perm.clone(), plan.kv_perm.clone(), out[0].clone(), out[1].clone(), out[2].clone()
+
+    for x, y in zip((Qs, Ks, Vs), sets[0]):
+        x.copy_(y)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()                                                       # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run()
+    for k in (1, 2, 0, 2):
+        for x, y in zip((Qs, Ks, Vs), sets[k]):
+            x.copy_(y)
+        g.replay()
+        torch.cuda.synchronize()
+        got = (maps[0].clone(), maps[1].clone(), O.clone(), c.clone(), sk.clone())
+        ref = eager(*sets[k])                                       # eager work between replays
+        for a_, b_ in zip(got, ref):
+            assert torch.equal(a_.view(torch.int16) if a_.dtype == torch.bfloat16 else a_,
+                               b_.view(torch.int16) if b_.dtype == torch.bfloat16 else b_), f"replay on set {k}"
+
+
 def test_separate_passes_equal_the_combined_call(tiny):
     """s2o_attention_local + s2o_attention_prefix (the local pass issued before the plan, as a
     caller overlapping the two would) give bit-identical results to s2o_attention with a
