@@ -179,7 +179,7 @@ WORKLOADS: Dict[str, Workload] = {
     "llama32k": Workload(name="llama32k", L=32768, S=2048, n_bursts=16, burst_len=32,
                          taus=(1e-3,), **_LLAMA),
     "llama128k": Workload(name="llama128k", L=131072, S=2048, heavy_rate=0.005,
-                          taus=(1e-4, 3e-4, 1e-3, 2e-3, 5e-3, 1e-2, 2e-2), **_LLAMA),
+                          taus=(1e-5, 1e-4, 3e-4, 1e-3, 2e-3, 5e-3, 1e-2, 2e-2), **_LLAMA),
     "mixed128k": Workload(name="mixed128k", L=131072, S=2048, heavy_rate=0.005,
                           k_boost=5.0, unstructured_groups=4, taus=(5e-3,), **_LLAMA),
 }
