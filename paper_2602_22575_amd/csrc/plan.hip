@@ -92,6 +92,7 @@ struct Scratch {
   uint32_t* counters; // [0]=#spans [1]=#big spans [2]=error flag
   int4* spans;        // [max_spans]  (row, begin, end, 0)
   int4* bigspans;     // [max_spans]
+  float* sk;          // [Z*H*P] s_K, used when the caller does not ask for the scores
   uint64_t* pairs;    // [Z*H*P]
   uint64_t* alt;      // [kBigGrid * L]
   int64_t max_spans;
@@ -127,6 +128,7 @@ static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S) {
   s.counters = (uint32_t*)take(64);
   s.spans = (int4*)take((size_t)s.max_spans * 16);
   s.bigspans = (int4*)take((size_t)s.max_spans * 16);
+  s.sk = (float*)take((size_t)Z * H * P * 4);
   s.pairs = (uint64_t*)take((size_t)Z * H * P * 8);
   s.alt = (uint64_t*)take((size_t)kBigGrid * L * 8);
   s.total = off;
@@ -420,13 +422,12 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
         // 64, so a 32-token block is valid for this row as a whole or not at all
         if (t0 + 32 * sb < lim) {
           if (MODE == 0) {
-            if (a.s_k) {
+            float* skdst = (a.s_k ? a.s_k : sc.sk) + base;
 #pragma unroll
-              for (int i4 = 0; i4 < 4; ++i4) {
-                const int t = t0 + 32 * sb + 8 * i4 + 4 * hh;
-                const f32x4 v = {acc[4 * i4], acc[4 * i4 + 1], acc[4 * i4 + 2], acc[4 * i4 + 3]};
-                *reinterpret_cast<f32x4*>(a.s_k + base + t) = v;
-              }
+            for (int i4 = 0; i4 < 4; ++i4) {
+              const int t = t0 + 32 * sb + 8 * i4 + 4 * hh;
+              const f32x4 v = {acc[4 * i4], acc[4 * i4 + 1], acc[4 * i4 + 2], acc[4 * i4 + 3]};
+              *reinterpret_cast<f32x4*>(skdst + t) = v;
             }
           } else {
             // all sixteen bucket searches first (independent LDS reads), then the counter
@@ -469,6 +470,74 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
     }
   }
 }
+
+__device__ inline int64_t row_base(const PlanArgs& a, int64_t row_id) {
+  const int n = (int)(row_id % a.N);
+  const int64_t zh = row_id / a.N;
+  return zh * kv_row_offset(a.N, a.S) + kv_row_offset(n, a.S);
+}
+
+// Bucket of a score = number of the row's (descending) splitters above it.  Two levels, both
+// by counting instead of a dependent binary search: every 8th splitter sits in a register
+// (top[k] = splitter 8k+7), the group of 7 below the hit comes from LDS with two 16-byte reads.
+__device__ inline int bucket_of_score(const float* spl, const float (&top)[7], float sv) {
+  int gi = 0;
+#pragma unroll
+  for (int k = 0; k < 7; ++k) gi += top[k] > sv ? 1 : 0;
+  const f32x4 lo = *reinterpret_cast<const f32x4*>(spl + 8 * gi);
+  const f32x4 hi = *reinterpret_cast<const f32x4*>(spl + 8 * gi + 4);
+  int bk = 8 * gi;
+  bk += lo[0] > sv ? 1 : 0; bk += lo[1] > sv ? 1 : 0; bk += lo[2] > sv ? 1 : 0; bk += lo[3] > sv ? 1 : 0;
+  bk += hi[0] > sv ? 1 : 0; bk += hi[1] > sv ? 1 : 0; bk += hi[2] > sv ? 1 : 0;
+  return bk;
+}
+
+// Counting and scatter passes of the sample sort, streaming over the stored scores: one
+// workgroup per (prefix row, chunk of sc.chunk tokens), a thread per token.  All lanes work on
+// the same row, so the splitter reads are broadcasts, the kernels need a few dozen registers
+// and one kilobyte of LDS, and enough wavefronts are resident to hide the LDS round trips
+// (re-computing the scores with MFMA in these passes kept them latency-bound at a quarter
+// of the issue rate).
+//   SCATTER = false: bucket counts of the cell -> chist
+//   SCATTER = true : (key, token) pairs to coffs[cell][bucket] + rank from an LDS cursor
+template <bool SCATTER>
+__global__ __launch_bounds__(256) void bucket_kernel(PlanArgs a, Scratch sc) {
+  __shared__ __attribute__((aligned(16))) float spl[kNBMax];
+  __shared__ uint32_t cnt[kNBMax];
+  const int64_t row_id = blockIdx.x / sc.maxch;
+  const int chunk = blockIdx.x % sc.maxch;
+  const int n = (int)(row_id % a.N);
+  const int lim = n * a.S;                      // prefix length of this row
+  const int t_begin = chunk * sc.chunk;
+  if (t_begin >= lim) return;
+  const int t_end = min(t_begin + sc.chunk, lim);
+  const int tid = threadIdx.x;
+  const int64_t cell = (row_id * sc.maxch + chunk) * kNBMax;
+  if (tid < kNBMax) {
+    spl[tid] = sc.splitters[row_id * kNBMax + tid];
+    cnt[tid] = SCATTER ? sc.coffs[cell + tid] : 0u;
+  }
+  __syncthreads();
+  float top[7];
+#pragma unroll
+  for (int k = 0; k < 7; ++k) top[k] = spl[8 * k + 7];
+  const int64_t base = row_base(a, row_id);
+  const float* sk = (a.s_k ? a.s_k : sc.sk) + base;
+  for (int t = t_begin + tid; t < t_end; t += 256) {
+    const float sv = sk[t];
+    const int bk = bucket_of_score(spl, top, sv);
+    const uint32_t pos = atomicAdd(&cnt[bk], 1u);
+    if (SCATTER) {
+      if (pos < (uint32_t)lim) sc.pairs[base + pos] = sort_key(sv, (uint32_t)t);
+      else sc.counters[2] = 1u;
+    }
+  }
+  if (!SCATTER) {
+    __syncthreads();
+    if (tid < kNBMax) sc.chist[cell + tid] = (uint16_t)cnt[tid];
+  }
+}
+
 
 // Per prefix row: sort the sampled scores (descending) and keep every (ns / nb)-th one as a
 // splitter; bucket k of the row then holds the scores s with exactly k splitters above s.
@@ -557,12 +626,6 @@ __global__ __launch_bounds__(4 * kNBMax) void scan_kernel(PlanArgs a, Scratch sc
       running += ch[c * kNBMax + b];
     }
   }
-}
-
-__device__ inline int64_t row_base(const PlanArgs& a, int64_t row_id) {
-  const int n = (int)(row_id % a.N);
-  const int64_t zh = row_id / a.N;
-  return zh * kv_row_offset(a.N, a.S) + kv_row_offset(n, a.S);
 }
 
 constexpr int kSortThreads = 1024;
@@ -722,6 +785,7 @@ __global__ __launch_bounds__(256) void big_sort_kernel(PlanArgs a, Scratch sc) {
 hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
   const Scratch sc = carve(a.scratch, a.Z, a.H, a.Hkv, a.L, a.S);
   if (sc.total > a.scratch_bytes) return hipErrorInvalidValue;
+  if ((int64_t)a.Z * a.H * a.N * sc.maxch > 0x7fffffff) return hipErrorInvalidValue;
   const int64_t rows = (int64_t)a.Z * a.H * a.N;
   const int G = a.H / a.Hkv;
   // dynamic LDS limits of the kernels that need more than the default
@@ -768,9 +832,10 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
       if ((size_t)ns2 * 8 > kSplitterLdsMax) return hipErrorInvalidValue;   // L > 1M tokens
       hipLaunchKernelGGL(splitter_kernel, dim3((unsigned)rows), dim3(256), (size_t)ns2 * 8, stream, a, sc);
     }
-    hipLaunchKernelGGL(score_kernel<1>, grid, dim3(256), lds, stream, a, sc);
+    const dim3 cgrid((unsigned)(rows * sc.maxch));
+    hipLaunchKernelGGL(bucket_kernel<false>, cgrid, dim3(256), 0, stream, a, sc);
     hipLaunchKernelGGL(scan_kernel, dim3((unsigned)rows), dim3(4 * kNBMax), 0, stream, a, sc);
-    hipLaunchKernelGGL(score_kernel<2>, grid, dim3(256), lds2, stream, a, sc);
+    hipLaunchKernelGGL(bucket_kernel<true>, cgrid, dim3(256), 0, stream, a, sc);
     const int64_t sort_grid = sc.max_spans < 8192 ? sc.max_spans : 8192;
     hipLaunchKernelGGL(span_sort_kernel, dim3((unsigned)sort_grid), dim3(kSortThreads), 0, stream, a, sc);
     hipLaunchKernelGGL(big_sort_kernel, dim3(kBigGrid), dim3(256), 0, stream, a, sc);
