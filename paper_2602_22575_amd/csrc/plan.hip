@@ -4,27 +4,23 @@
 //   pool_sq_sort_kernel  one workgroup per (z, h, segment): a single pass over the
 //                        segment's Q rows gives q_mean and s_Q; the S scores are then
 //                        Argsort-ed in LDS (bitonic network on 64-bit keys) -> Q_perm.
-//   score_kernel<MODE>   s_K[n, t] = <q_mean[n], K[t]> as an MFMA contraction per KV head:
+//   score_kernel         s_K[n, t] = <q_mean[n], K[t]> as an MFMA contraction per KV head:
 //                        columns = (query head of the group, segment), rows = key tokens
 //                        staged through LDS.  q_mean is split exactly into three bf16 terms
 //                        so that bf16 MFMA reproduces the fp32 x bf16 products exactly (fp32
-//                        accumulation).  The Argsort of a prefix row (up to L - S scores) is
-//                        a sample sort: buckets are delimited by splitters taken from a
-//                        sorted sample of the row, so their populations are balanced for
-//                        any score distribution.  The kernel runs three times with different
-//                        epilogues:
-//                          MODE 0  one sampled score per 64 tokens (+ optional s_K store)
-//                          MODE 1  per (row, chunk of up to 1024 tokens) bucket counts, kept in LDS
-//                                  and written once per chunk (no global atomics)
-//                          MODE 2  scatter of (key, token) pairs to their bucket: global
-//                                  offset of the (row, chunk, bucket) cell + a rank taken
-//                                  from an LDS counter
-//                        Re-computing the scores costs K reads (0.27 GB at 128K, from the
-//                        last-level cache after the first pass) instead of a round trip of
-//                        the 0.53 GB score array.
+//                        accumulation).  The scores are stored (in the caller's s_K array or
+//                        in scratch) together with one sampled score per 64 tokens.
+//                        The Argsort of a prefix row (up to L - S scores) is a sample sort:
+//                        buckets are delimited by splitters taken from a sorted sample of
+//                        the row, so their populations are balanced for any distribution.
+//   count_kernel         per (row, cell of up to 4096 tokens): bucket counts, kept in LDS and
+//                        written once per cell (no global atomics).
+//   scatter_kernel       per (row, cell): (key, token) pairs to their bucket -- offset of the
+//                        (row, cell, bucket) run + a rank from an LDS cursor -- staged in LDS
+//                        sorted by bucket so that the global stores are runs, not scatters.
 //   splitter_kernel      per prefix row: sorts the sample in LDS and keeps every
 //                        (sample size / buckets)-th value as a splitter.
-//   scan_kernel          per prefix row: cell offsets (bucket-major, chunk-minor) and the
+//   scan_kernel          per prefix row: run offsets (bucket-major, cell-minor) and the
 //                        list of spans (runs of consecutive buckets that fit the LDS sort).
 //   span_sort_kernel     sorts each span in LDS and writes the token indices at their
 //                        final ranks -> KV_perm.  Linear-time: a second, fine bucketing on
@@ -50,11 +46,11 @@ constexpr int kD = 128;
 constexpr int kNBMax = 64;         // buckets per prefix row (upper bound)
 constexpr int kBucketAvg = 2048;   // target average bucket population
 constexpr int kSampleStride = 64;  // one sampled score per this many tokens
-constexpr int kSplStride = kNBMax + 4;   // floats per row of splitters in LDS (rows 16-byte aligned)
 constexpr int kSpanCap = 4096;     // elements one span_sort workgroup sorts in LDS
 constexpr int kSubBuckets = 2048;  // fine buckets of the in-LDS sort
 constexpr int kSubMax = 64;        // a fuller sub-bucket sends the span to the bitonic fallback
 constexpr int kChunkMax = 1024;    // key tokens per score workgroup (halved while the grid is too small)
+constexpr int kCellMax = 1024;     // key tokens per (row, cell) of the bucket counts (16-bit counters)
 constexpr int kSub = 64;           // key tokens per LDS tile of the score kernel (32 in the scatter pass)
 constexpr int kKStride = 136;      // bf16 elements per K row in LDS (272 B)
 constexpr int kBigGrid = 64;       // workgroups of the fallback sort
@@ -87,7 +83,7 @@ struct Scratch {
   uint16_t* qsplit;   // [Z*H*N][3][128] bf16
   float* samples;     // [Z*H*N][L/64] one score per 64 tokens of the row's prefix
   float* splitters;   // [Z*H*N][kNBMax] descending; entries past the row's buckets are -inf
-  uint16_t* chist;    // [Z*H*N][maxch][kNBMax] bucket counts per chunk of `chunk` tokens
+  uint16_t* chist;    // [Z*H*N][maxch][kNBMax] bucket counts per cell of `cell` tokens
   uint32_t* coffs;    // same shape: offset of the cell inside its row
   uint32_t* counters; // [0]=#spans [1]=#big spans [2]=error flag
   int4* spans;        // [max_spans]  (row, begin, end, 0)
@@ -96,7 +92,8 @@ struct Scratch {
   uint64_t* pairs;    // [Z*H*P]
   uint64_t* alt;      // [kBigGrid * L]
   int64_t max_spans;
-  int maxch;
+  int maxch;          // cells per row
+  int cell;           // key tokens per (row, cell) of the bucket counts
   int chunk;          // key tokens per score workgroup: kChunkMax, less for short sequences
   size_t total;
 };
@@ -115,7 +112,11 @@ static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S) {
     s.chunk = kChunkMax;
     while (s.chunk > kSub && (int64_t)Z * Hkv * rbg * ((L + s.chunk - 1) / s.chunk) < 1024) s.chunk /= 2;
   }
-  s.maxch = (L + s.chunk - 1) / s.chunk;
+  // bucket counts are kept per (row, cell of tokens); one workgroup of the counting and scatter
+  // passes handles one cell: as large as the staging area allows unless the grid gets too small
+  s.cell = kCellMax;
+  while (s.cell > 256 && rows * ((L / 2 + s.cell - 1) / s.cell) < 2048) s.cell /= 2;
+  s.maxch = (L + s.cell - 1) / s.cell;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return (char*)base + o; };
   s.kguide = (float*)take((size_t)Z * Hkv * kD * 4);
@@ -266,22 +267,15 @@ __global__ __launch_bounds__(256) void pool_sq_sort_kernel(PlanArgs a, Scratch s
 //   B (16 dims x 32 rows)  : q_mean split terms, lane (row = l%32, hh) holds the same dims
 //   C (32 tokens x 32 rows): register i of lane l = [token 8*(i/4) + 4*hh + i%4][row l%32],
 //                            so a lane sees one row only and its meta data are scalars
-template <int MODE>
 __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
-  // the scatter pass keeps a 32-bit cursor per (row, bucket) in LDS and pays for it with a
-  // smaller K tile
-  constexpr int kSubT = MODE == 2 ? 32 : kSub;
-  constexpr int kCntWords = MODE == 2 ? kNBMax : kNBMax / 2;   // LDS words per row of counters
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t* Kt = reinterpret_cast<uint16_t*>(smem);                          // [kSubT][kKStride]
-  uint32_t* hist_all = reinterpret_cast<uint32_t*>(smem + kSubT * kKStride * 2);  // [4][32][kCntWords]
-  float* spl_all = reinterpret_cast<float*>(hist_all + 4 * 32 * kCntWords);      // [4][32][kSplStride]
+  uint16_t* Kt = reinterpret_cast<uint16_t*>(smem);                          // [kSub][kKStride]
 
   const int G = a.H / a.Hkv;
   const int R = G * a.N;
   const int nchunks = (a.L + sc.chunk - 1) / sc.chunk;
   // all work on one KV head goes to one XCD (block ids are dealt round-robin to the 8 XCDs):
-  // the scatter pass appends to ~R*kNBMax open cache lines per head, which fit one L2
+  // the row blocks of a head read the same K chunks
   int unit, rest;
   {
     const int U = a.Z * a.Hkv, b = blockIdx.x;
@@ -317,6 +311,7 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
   const int64_t zh = (int64_t)z * a.H + g * G + rr / a.N;
   const int64_t row_id = zh * a.N + rr % a.N;
   const int64_t base = zh * kv_row_offset(a.N, a.S) + kv_row_offset(rr % a.N, a.S);
+  float* skdst = (a.s_k ? a.s_k : sc.sk) + base;
 
   // B fragments: 3 split terms x 8 contraction steps
   bf16x8 bq[3][8];
@@ -328,70 +323,34 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
       for (int kk = 0; kk < 8; ++kk)
         bq[t][kk] = *reinterpret_cast<const bf16x8*>(qs + t * kD + 16 * kk + 8 * hh);
   }
-
-  // MODE 1: two 16-bit counters per word; MODE 2: one cursor per word, preset to the cell's
-  // offset inside its row
-  uint32_t* hist = hist_all + wave * 32 * kCntWords;
-  float* spl = spl_all + wave * 32 * kSplStride;           // this wavefront's rows' splitters
-  if (MODE != 0) {
-    if (MODE == 1)
-      for (int i = lane; i < 32 * kCntWords; i += 64) hist[i] = 0;
-    for (int i = 0; i < 32; ++i) {
-      const int r2 = min(32 * rb + i, R - 1);
-      const int64_t rid2 = ((int64_t)z * a.H + g * G + r2 / a.N) * a.N + r2 % a.N;
-      spl[i * kSplStride + lane] = sc.splitters[rid2 * kNBMax + lane];
-      if (MODE == 2) hist[i * kCntWords + lane] = sc.coffs[(rid2 * sc.maxch + chunk) * kNBMax + lane];
-    }
-  }
-  const float* myspl = spl + m_ * kSplStride;
-  // Bucket of a score = number of the row's (descending) splitters above it.  Two levels,
-  // both by counting instead of a dependent binary search: every 8th splitter sits in a
-  // register, the group of 7 below the hit comes from LDS with two independent 16-byte reads.
-  float top[7];
-  if (MODE != 0) {
-    __syncthreads();                         // the rows written above are read by other lanes
-#pragma unroll
-    for (int k = 0; k < 7; ++k) top[k] = myspl[8 * k + 7];
-  }
-  auto bucket_of = [&](float sv) {
-    int gi = 0;
-#pragma unroll
-    for (int k = 0; k < 7; ++k) gi += top[k] > sv ? 1 : 0;
-    const f32x4 lo = *reinterpret_cast<const f32x4*>(myspl + 8 * gi);
-    const f32x4 hi = *reinterpret_cast<const f32x4*>(myspl + 8 * gi + 4);
-    int bk = 8 * gi;
-    bk += lo[0] > sv ? 1 : 0; bk += lo[1] > sv ? 1 : 0; bk += lo[2] > sv ? 1 : 0; bk += lo[3] > sv ? 1 : 0;
-    bk += hi[0] > sv ? 1 : 0; bk += hi[1] > sv ? 1 : 0; bk += hi[2] > sv ? 1 : 0;
-    return bk;
-  };
   const int samples_per_row = a.L / kSampleStride;
 
   // K tile loader: thread (c, q) moves 16-byte chunk c of rows q, q+16, ...
   const uint16_t* Kh = a.K + z * a.ks[0] + g * a.ks[1];
   const int c = tid & 15, q = tid >> 4;
-  u32x4 kreg[kSubT / 16];
+  u32x4 kreg[kSub / 16];
   auto load_tile = [&](int t0) {
 #pragma unroll
-    for (int s = 0; s < kSubT / 16; ++s) {
+    for (int s = 0; s < kSub / 16; ++s) {
       const int t = min(t0 + q + 16 * s, a.L - 1);
       kreg[s] = *reinterpret_cast<const u32x4*>(Kh + (int64_t)t * a.ks[2] + 8 * c);
     }
   };
   auto store_tile = [&]() {
 #pragma unroll
-    for (int s = 0; s < kSubT / 16; ++s)
+    for (int s = 0; s < kSub / 16; ++s)
       *reinterpret_cast<u32x4*>(Kt + (q + 16 * s) * kKStride + 8 * c) = kreg[s];
   };
 
   load_tile(t_begin);
-  for (int t0 = t_begin; t0 < t_end; t0 += kSubT) {
+  for (int t0 = t_begin; t0 < t_end; t0 += kSub) {
     __syncthreads();                       // previous tile fully consumed
     store_tile();
     __syncthreads();
-    if (t0 + kSubT < t_end) load_tile(t0 + kSubT);
+    if (t0 + kSub < t_end) load_tile(t0 + kSub);
     if (t0 < lim_wave) {
 #pragma unroll 1
-      for (int sb = 0; sb < kSubT / 32; ++sb) {
+      for (int sb = 0; sb < kSub / 32; ++sb) {
         f32x16 acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
@@ -406,66 +365,26 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
 #pragma unroll
           for (int kk = 0; kk < 8; ++kk)
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], bq[tt][kk], acc, 0, 0, 0);
-        if (MODE == 0) {
+        // lim is a multiple of 64, so a 32-token block is valid for this row as a whole or not at all
+        if (t0 + 32 * sb < lim) {
           // sample: one token of every 64, at a position that varies from block to block
           const int blk = (t0 + 32 * sb) / kSampleStride;
           const int off = ((blk * 37 + 11) & 63) - 32 * (sb & 1);   // offset inside this 32-token block
-          if (off >= 0 && off < 32 && ((off >> 2) & 1) == hh && t0 + 32 * sb < lim) {
+          if (off >= 0 && off < 32 && ((off >> 2) & 1) == hh) {
             const int idx = 4 * (off >> 3) + (off & 3);               // register holding that token
             float v = acc[0];
 #pragma unroll
             for (int i = 1; i < 16; ++i) v = idx == i ? acc[i] : v;
             sc.samples[row_id * samples_per_row + blk] = v;
           }
-        }
-        // the four registers of a group are four consecutive tokens; lim is a multiple of
-        // 64, so a 32-token block is valid for this row as a whole or not at all
-        if (t0 + 32 * sb < lim) {
-          if (MODE == 0) {
-            float* skdst = (a.s_k ? a.s_k : sc.sk) + base;
+          // the four registers of a group are four consecutive tokens
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-              const int t = t0 + 32 * sb + 8 * i4 + 4 * hh;
-              const f32x4 v = {acc[4 * i4], acc[4 * i4 + 1], acc[4 * i4 + 2], acc[4 * i4 + 3]};
-              *reinterpret_cast<f32x4*>(skdst + t) = v;
-            }
-          } else {
-            // all sixteen bucket searches first (independent LDS reads), then the counter
-            // updates: interleaved, every search would wait behind the previous key's atomic
-            int bk[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) bk[i] = bucket_of(acc[i]);
-            if (MODE == 1) {
-#pragma unroll
-              for (int i = 0; i < 16; ++i)
-                atomicAdd(&hist[m_ * kCntWords + (bk[i] >> 1)], 1u << (16 * (bk[i] & 1)));
-            } else {
-              uint32_t pos[16];
-#pragma unroll
-              for (int i = 0; i < 16; ++i) pos[i] = atomicAdd(&hist[m_ * kCntWords + bk[i]], 1u);
-#pragma unroll
-              for (int i = 0; i < 16; ++i) {
-                const int t = t0 + 32 * sb + 8 * (i >> 2) + 4 * hh + (i & 3);
-                if (pos[i] < (uint32_t)lim) sc.pairs[base + pos[i]] = sort_key(acc[i], (uint32_t)t);
-                else sc.counters[2] = 1u;
-              }
-            }
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const int t = t0 + 32 * sb + 8 * i4 + 4 * hh;
+            const f32x4 v = {acc[4 * i4], acc[4 * i4 + 1], acc[4 * i4 + 2], acc[4 * i4 + 3]};
+            *reinterpret_cast<f32x4*>(skdst + t) = v;
           }
         }
-      }
-    }
-  }
-  if (MODE == 1) {
-    // counts of this (row block, chunk): one 256-byte row of kNBMax 16-bit counters per row
-    __builtin_amdgcn_s_waitcnt(0);
-    __builtin_amdgcn_wave_barrier();
-    for (int i = 0; i < 32; ++i) {
-      const int r2 = 32 * rb + i;
-      if (row_limit(r2) > t_begin) {
-        const int64_t zh2 = (int64_t)z * a.H + g * G + r2 / a.N;
-        const int64_t cell2 = ((zh2 * a.N + r2 % a.N) * sc.maxch + chunk) * kNBMax;
-        if (lane < kNBMax / 2)
-          reinterpret_cast<uint32_t*>(sc.chist + cell2)[lane] = hist[i * kCntWords + lane];
       }
     }
   }
@@ -493,29 +412,65 @@ __device__ inline int bucket_of_score(const float* spl, const float (&top)[7], f
 }
 
 // Counting and scatter passes of the sample sort, streaming over the stored scores: one
-// workgroup per (prefix row, chunk of sc.chunk tokens), a thread per token.  All lanes work on
-// the same row, so the splitter reads are broadcasts, the kernels need a few dozen registers
-// and one kilobyte of LDS, and enough wavefronts are resident to hide the LDS round trips
+// workgroup per (prefix row, cell of sc.cell tokens), threads striding over the tokens.  All
+// lanes work on the same row, so the splitter reads are broadcasts, the kernels need a few
+// dozen registers, and enough wavefronts are resident to hide the LDS round trips
 // (re-computing the scores with MFMA in these passes kept them latency-bound at a quarter
 // of the issue rate).
-//   SCATTER = false: bucket counts of the cell -> chist
-//   SCATTER = true : (key, token) pairs to coffs[cell][bucket] + rank from an LDS cursor
-template <bool SCATTER>
-__global__ __launch_bounds__(256) void bucket_kernel(PlanArgs a, Scratch sc) {
+__global__ __launch_bounds__(256) void count_kernel(PlanArgs a, Scratch sc) {
   __shared__ __attribute__((aligned(16))) float spl[kNBMax];
   __shared__ uint32_t cnt[kNBMax];
   const int64_t row_id = blockIdx.x / sc.maxch;
-  const int chunk = blockIdx.x % sc.maxch;
-  const int n = (int)(row_id % a.N);
-  const int lim = n * a.S;                      // prefix length of this row
-  const int t_begin = chunk * sc.chunk;
+  const int cellno = blockIdx.x % sc.maxch;
+  const int lim = (int)(row_id % a.N) * a.S;    // prefix length of this row
+  const int t_begin = cellno * sc.cell;
   if (t_begin >= lim) return;
-  const int t_end = min(t_begin + sc.chunk, lim);
+  const int t_end = min(t_begin + sc.cell, lim);
   const int tid = threadIdx.x;
-  const int64_t cell = (row_id * sc.maxch + chunk) * kNBMax;
   if (tid < kNBMax) {
     spl[tid] = sc.splitters[row_id * kNBMax + tid];
-    cnt[tid] = SCATTER ? sc.coffs[cell + tid] : 0u;
+    cnt[tid] = 0u;
+  }
+  __syncthreads();
+  float top[7];
+#pragma unroll
+  for (int k = 0; k < 7; ++k) top[k] = spl[8 * k + 7];
+  const float* sk = (a.s_k ? a.s_k : sc.sk) + row_base(a, row_id);
+  for (int t = t_begin + tid; t < t_end; t += 256) atomicAdd(&cnt[bucket_of_score(spl, top, sk[t])], 1u);
+  __syncthreads();
+  if (tid < kNBMax) sc.chist[(row_id * sc.maxch + cellno) * kNBMax + tid] = (uint16_t)cnt[tid];
+}
+
+// Scatter: the cell's (key, token) pairs are first placed in LDS sorted by bucket (rank from an
+// LDS cursor that starts at the bucket's offset inside the cell), each with its destination
+// (the cell's offset in the bucket's global range + its rank); the staged pairs are then
+// written out in staged order, so that the lanes of a store instruction hit runs of
+// consecutive addresses (a bucket's run of this cell) instead of 64 different cache lines.
+__global__ __launch_bounds__(256) void scatter_kernel(PlanArgs a, Scratch sc) {
+  __shared__ __attribute__((aligned(16))) float spl[kNBMax];
+  __shared__ uint32_t cur[kNBMax];              // next free staging slot of each bucket
+  __shared__ uint32_t delta[kNBMax];            // global offset of the bucket's run - its first slot
+  __shared__ uint64_t stage[kCellMax];
+  __shared__ uint32_t sdst[kCellMax];
+  const int64_t row_id = blockIdx.x / sc.maxch;
+  const int cellno = blockIdx.x % sc.maxch;
+  const int lim = (int)(row_id % a.N) * a.S;
+  const int t_begin = cellno * sc.cell;
+  if (t_begin >= lim) return;
+  const int t_end = min(t_begin + sc.cell, lim);
+  const int tid = threadIdx.x;
+  const int64_t cell = (row_id * sc.maxch + cellno) * kNBMax;
+  if (tid < kNBMax) {                           // one wavefront: exclusive scan of the cell's counts
+    spl[tid] = sc.splitters[row_id * kNBMax + tid];
+    const uint32_t v = sc.chist[cell + tid];
+    uint32_t incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t u = __shfl_up(incl, o);
+      if (tid >= o) incl += u;
+    }
+    cur[tid] = incl - v;
+    delta[tid] = sc.coffs[cell + tid] - (incl - v);
   }
   __syncthreads();
   float top[7];
@@ -526,15 +481,20 @@ __global__ __launch_bounds__(256) void bucket_kernel(PlanArgs a, Scratch sc) {
   for (int t = t_begin + tid; t < t_end; t += 256) {
     const float sv = sk[t];
     const int bk = bucket_of_score(spl, top, sv);
-    const uint32_t pos = atomicAdd(&cnt[bk], 1u);
-    if (SCATTER) {
-      if (pos < (uint32_t)lim) sc.pairs[base + pos] = sort_key(sv, (uint32_t)t);
-      else sc.counters[2] = 1u;
+    const uint32_t slot = atomicAdd(&cur[bk], 1u);
+    if (slot < (uint32_t)kCellMax) {
+      stage[slot] = sort_key(sv, (uint32_t)t);
+      sdst[slot] = delta[bk] + slot;
+    } else {
+      sc.counters[2] = 1u;
     }
   }
-  if (!SCATTER) {
-    __syncthreads();
-    if (tid < kNBMax) sc.chist[cell + tid] = (uint16_t)cnt[tid];
+  __syncthreads();
+  const int n_here = t_end - t_begin;
+  for (int i = tid; i < n_here; i += 256) {
+    const uint32_t d = sdst[i];
+    if (d < (uint32_t)lim) sc.pairs[base + d] = stage[i];
+    else sc.counters[2] = 1u;
   }
 }
 
@@ -577,7 +537,7 @@ __global__ __launch_bounds__(4 * kNBMax) void scan_kernel(PlanArgs a, Scratch sc
   if (n == 0) return;
   const int b = threadIdx.x % kNBMax, q = threadIdx.x / kNBMax;
   const int nb = row_buckets(n, a.S);
-  const int nch = (n * a.S + sc.chunk - 1) / sc.chunk;
+  const int nch = (n * a.S + sc.cell - 1) / sc.cell;
   const int c0 = (nch * q) / 4, c1 = (nch * (q + 1)) / 4;   // this thread's chunk range
   const uint16_t* ch = sc.chist + row_id * sc.maxch * kNBMax;
   uint32_t* co = sc.coffs + row_id * sc.maxch * kNBMax;
@@ -789,8 +749,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
   const int64_t rows = (int64_t)a.Z * a.H * a.N;
   const int G = a.H / a.Hkv;
   // dynamic LDS limits of the kernels that need more than the default
-  constexpr size_t kScoreLds = (size_t)kSub * kKStride * 2 + 4 * 32 * (kNBMax / 2) * 4 + 4 * 32 * kSplStride * 4;
-  constexpr size_t kScatterLds = (size_t)32 * kKStride * 2 + 4 * 32 * kNBMax * 4 + 4 * 32 * kSplStride * 4;
+  constexpr size_t kScoreLds = (size_t)kSub * kKStride * 2;
   constexpr size_t kSplitterLdsMax = 128 * 1024;   // a row's sample (L / 64 scores, 8-byte keys) is sorted in LDS
   {
     static std::mutex mu;
@@ -798,12 +757,6 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
     const hipError_t se = once_per_device(mu, done, [] {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pool_sq_sort_kernel),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8 + 16 * kD * 4);
-      if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<0>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScoreLds);
-      if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<1>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScoreLds);
-      if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<2>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kScatterLds);
       if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&splitter_kernel),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSplitterLdsMax);
       return e;
@@ -822,10 +775,9 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
   if (a.N > 1) {
     const int RB = (G * a.N + 31) / 32;
     const int RBG = (RB + 3) / 4;
-    const int nchunks = sc.maxch;
+    const int nchunks = (a.L + sc.chunk - 1) / sc.chunk;
     const dim3 grid((unsigned)((int64_t)a.Z * a.Hkv * RBG * nchunks));
-    const size_t lds = kScoreLds, lds2 = kScatterLds;
-    hipLaunchKernelGGL(score_kernel<0>, grid, dim3(256), lds, stream, a, sc);
+    hipLaunchKernelGGL(score_kernel, grid, dim3(256), kScoreLds, stream, a, sc);
     {
       int ns2 = 1;
       while (ns2 < a.L / kSampleStride) ns2 <<= 1;
@@ -833,9 +785,9 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
       hipLaunchKernelGGL(splitter_kernel, dim3((unsigned)rows), dim3(256), (size_t)ns2 * 8, stream, a, sc);
     }
     const dim3 cgrid((unsigned)(rows * sc.maxch));
-    hipLaunchKernelGGL(bucket_kernel<false>, cgrid, dim3(256), 0, stream, a, sc);
+    hipLaunchKernelGGL(count_kernel, cgrid, dim3(256), 0, stream, a, sc);
     hipLaunchKernelGGL(scan_kernel, dim3((unsigned)rows), dim3(4 * kNBMax), 0, stream, a, sc);
-    hipLaunchKernelGGL(bucket_kernel<true>, cgrid, dim3(256), 0, stream, a, sc);
+    hipLaunchKernelGGL(scatter_kernel, cgrid, dim3(256), 0, stream, a, sc);
     const int64_t sort_grid = sc.max_spans < 8192 ? sc.max_spans : 8192;
     hipLaunchKernelGGL(span_sort_kernel, dim3((unsigned)sort_grid), dim3(kSortThreads), 0, stream, a, sc);
     hipLaunchKernelGGL(big_sort_kernel, dim3(kBigGrid), dim3(256), 0, stream, a, sc);
