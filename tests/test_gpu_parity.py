@@ -438,6 +438,14 @@ def test_llama32k_sampled(gpu):
                   variants=[(1, True, 0), (0, False, 0), (0, True, 40), (2, True, 25)])
 
 
+@pytest.mark.parametrize("S", [512, 4096])
+def test_llama32k_other_segment_lengths(gpu, S):
+    """The same 32K workload with shorter and longer segments than the default 2048 (64 and 8
+    segments): plan parity on two heads, attention parity on sampled pairs."""
+    N = 32768 // S
+    _sampled_case("llama32k", plan_heads=[5, 30], attn_samples=[(5, [1, N // 2]), (30, [N - 1])], taus=(2e-3,), S=S)
+
+
 def test_llama128k_sampled(gpu):
     """The headline shape (128K): plan parity on two heads, attention parity on sampled
     (head, segment) pairs, at the threshold bench.py times and with skipping disabled on
