@@ -78,7 +78,7 @@ __device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0
 
 // ---------------------------------------------------------------------------------------
 struct Scratch {
-  float* kguide;      // [Z*Hkv*128]
+  float* kguide;      // [Z*Hkv][kGuideParts][128] partial column sums of the first key segment
   float* qmean;       // [Z*H*N*128]
   uint16_t* qsplit;   // [Z*H*N][3][128] bf16
   float* samples;     // [Z*H*N][L/64] one score per 64 tokens of the row's prefix
@@ -119,7 +119,7 @@ static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S) {
   s.maxch = (L + s.cell - 1) / s.cell;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return (char*)base + o; };
-  s.kguide = (float*)take((size_t)Z * Hkv * kD * 4);
+  s.kguide = (float*)take((size_t)Z * Hkv * 8 * kD * 4);
   s.qmean = (float*)take((size_t)rows * kD * 4);
   s.qsplit = (uint16_t*)take((size_t)rows * 3 * kD * 2);
   s.samples = (float*)take((size_t)rows * (L / kSampleStride) * 4);
@@ -147,13 +147,20 @@ __global__ void init_kernel(Scratch s, int64_t rows) {
 }
 
 // k_guide[z,g,:] = mean_{s<S} K[z,g,s,:]
+constexpr int kGuideParts = 8;     // workgroups per KV head summing the first key segment
+
+// Partial column sums of the first key segment: workgroup (z, g, part) adds the rows of its
+// eighth of the segment; the consumers add the eight partial sums in a fixed order, so k_guide
+// is reproducible bit for bit without a serial pass over the segment by one workgroup.
 __global__ __launch_bounds__(256) void kguide_kernel(PlanArgs a, Scratch sc) {
   __shared__ float red[16][kD];
-  const int z = blockIdx.x / a.Hkv, g = blockIdx.x % a.Hkv;
+  const int unit = blockIdx.x / kGuideParts, part = blockIdx.x % kGuideParts;
+  const int z = unit / a.Hkv, g = unit % a.Hkv;
   const int c = threadIdx.x & 15, r = threadIdx.x >> 4;
   const uint16_t* Kh = a.K + z * a.ks[0] + g * a.ks[1];
+  const int rows = a.S / kGuideParts;            // S is a multiple of 64
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int row = r; row < a.S; row += 16) {
+  for (int row = part * rows + r; row < (part + 1) * rows; row += 16) {
     const u32x4 v = *reinterpret_cast<const u32x4*>(Kh + (int64_t)row * a.ks[2] + 8 * c);
 #pragma unroll
     for (int q = 0; q < 4; ++q) { acc[2 * q] += bf16_lo(v[q]); acc[2 * q + 1] += bf16_hi(v[q]); }
@@ -165,9 +172,7 @@ __global__ __launch_bounds__(256) void kguide_kernel(PlanArgs a, Scratch sc) {
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) s += red[i][threadIdx.x];
-    s *= 1.0f / (float)a.S;
     sc.kguide[(int64_t)blockIdx.x * kD + threadIdx.x] = s;
-    if (a.k_guide) a.k_guide[(int64_t)blockIdx.x * kD + threadIdx.x] = s;
   }
 }
 
@@ -204,10 +209,20 @@ __global__ __launch_bounds__(256) void pool_sq_sort_kernel(PlanArgs a, Scratch s
   const int g = h / G;
   const int tid = threadIdx.x, c = tid & 15, r = tid >> 4;
   const uint16_t* Qs = a.Q + z * a.qs[0] + h * a.qs[1] + (int64_t)n * a.S * a.qs[2];
-  const float* kg = sc.kguide + ((int64_t)z * a.Hkv + g) * kD + 8 * c;
+  // k_guide = mean of the first key segment, from the partial sums in a fixed order
+  const float* kg = sc.kguide + ((int64_t)z * a.Hkv + g) * kGuideParts * kD + 8 * c;
   float kgv[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) kgv[j] = kg[j];
+  for (int j = 0; j < 8; ++j) {
+    float t = 0.f;
+#pragma unroll
+    for (int pp = 0; pp < kGuideParts; ++pp) t += kg[pp * kD + j];
+    kgv[j] = t * (1.0f / (float)a.S);
+  }
+  if (a.k_guide && n == 0 && h % G == 0 && r == 0) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) a.k_guide[((int64_t)z * a.Hkv + g) * kD + 8 * c + j] = kgv[j];
+  }
 
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int row = r; row < a.S; row += 16) {
@@ -765,7 +780,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
   }
 
   hipLaunchKernelGGL(init_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream, sc, rows);
-  hipLaunchKernelGGL(kguide_kernel, dim3(a.Z * a.Hkv), dim3(256), 0, stream, a, sc);
+  hipLaunchKernelGGL(kguide_kernel, dim3(a.Z * a.Hkv * kGuideParts), dim3(256), 0, stream, a, sc);
   {
     int n2 = 1;
     while (n2 < a.S) n2 <<= 1;
