@@ -531,8 +531,7 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
   static std::mutex mu;
   static uint64_t done = 0;
   const hipError_t se = once_per_device(mu, done, [] {
-    const void* fns[3] = {reinterpret_cast<const void*>(&s2o_attention_kernel<0>),
-                          reinterpret_cast<const void*>(&s2o_attention_kernel<1>),
+    const void* fns[2] = {reinterpret_cast<const void*>(&s2o_attention_kernel<0>),
                           reinterpret_cast<const void*>(&s2o_attention_kernel<2>)};
     for (const void* f : fns) {
       const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds);
@@ -550,7 +549,10 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
   if (a.passes == 0) {
     hipLaunchKernelGGL(s2o_attention_kernel<0>, grid, block, kAttnLds, stream, a);
   } else {
-    if (a.passes & 1) hipLaunchKernelGGL(s2o_attention_kernel<1>, grid, block, kAttnLds, stream, a);
+    if (a.passes & 1) {
+      const hipError_t e = launch_local(a, stream);
+      if (e != hipSuccess) return e;
+    }
     if (a.passes & 2) hipLaunchKernelGGL(s2o_attention_kernel<2>, grid, block, kAttnLds, stream, a);
   }
   return hipGetLastError();

@@ -67,5 +67,7 @@ size_t plan_scratch_bytes(int Z, int H, int Hkv, int L, int S);
 size_t attention_state_bytes(int Z, int H, int L);
 hipError_t launch_plan(const PlanArgs& a, hipStream_t stream);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t stream);
+// Alg. 2 alone (local.hip): own-segment pass in original query order into the state buffers
+hipError_t launch_local(const AttnArgs& a, hipStream_t stream);
 
 }  // namespace s2o
