@@ -12,7 +12,8 @@
 // per wavefront and is taken one tile late (the PV product of a tile waits for its vote).  The
 // dense intra-segment causal window (Pass-1) is run by the same loop before the prefix
 // walk, with identity indices and a per-element causal mask, so its state never leaves
-// registers.
+// registers.  (That is the single-launch form; with a state buffer the own-segment pass runs
+// as its own kernel, local.hip, and this kernel only walks the prefix.)
 //
 // MFMA formulation (v_mfma_f32_32x32x16_bf16), transposed so that a query row lives in
 // one lane pair and softmax statistics need a single cross-lane step:
@@ -69,9 +70,9 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
 }
 
 // PASS 0: everything in one launch (own-segment window, then the prefix walk).
-// PASS 1: Alg. 2 alone -- queries in original order, exactly the causal own-segment tiles,
-//         leaves (acc, l, m) per row in the state buffers (A, Lbuf, Mbuf of the paper).
-// PASS 2: Alg. 3 alone -- gathers the queries and their states by Q_perm and walks the prefix.
+// PASS 2: Alg. 3 alone -- gathers the queries by Q_perm, resumes each row from the state
+//         (acc, l, m: the A, Lbuf, Mbuf buffers of the paper) that the own-segment pass
+//         (Alg. 2, local.hip) left in the state buffers, and walks the prefix.
 // Two launches cost a round trip of the fp32 state through HBM but halve the own-segment
 // work: a permuted query tile needs every own-segment key tile (with a per-element mask),
 // a tile in original order only those up to its diagonal.
@@ -126,8 +127,8 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   const int32_t* kvrow = a.kv_perm + zh * kv_row_offset(a.N, a.S) + kv_row_offset(n, a.S);
   const int nS = n * a.S;
   const int nK_all = nS / kBN;                 // prefix tiles that exist for this segment
-  // prefix tiles this launch may walk: none in the own-segment pass, at most the budget
-  const int nK = PASS == 1 ? 0 : (a.max_tiles > 0 ? min(nK_all, a.max_tiles) : nK_all);
+  // prefix tiles this launch may walk: at most the budget
+  const int nK = a.max_tiles > 0 ? min(nK_all, a.max_tiles) : nK_all;
 
   // wavefront -> (query tile of the workgroup, 32-row part); the parts of a tile are
   // wavefronts tile, tile + tpw, ...
@@ -140,7 +141,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   bf16x8 qf[8];
   {
     const int r = min(j, TJ - 1) * BM + kRowsPerWave * part + m_;
-    qoff = (a.use_q_perm && PASS != 1) ? a.q_perm[(zh * a.N + n) * a.S + r] : r;
+    qoff = a.use_q_perm ? a.q_perm[(zh * a.N + n) * a.S + r] : r;
     qoff = min(max(qoff, 0), a.S - 1);
     const uint16_t* qrow = Qh + (int64_t)(nS + qoff) * a.qs[2];
 #pragma unroll
@@ -382,9 +383,9 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     const bool own = it < nloc;
     if (own ? it * kBN <= wave_pmax : active) {   // wave_pmax = -1 for a wavefront without a query tile
       qk(it & 1);
-      // the causal mask only matters if some row of the wavefront ends inside this tile
-      // (never skipped for permuted rows, whose positions are scattered)
-      if (!own || (PASS == 1 && it * kBN + kBN - 1 <= wave_pmax - (kRowsPerWave - 1))) softmax(std::false_type{}, it);
+      // own-segment tiles always carry the causal mask: the rows of a permuted query tile are
+      // scattered over the segment
+      if (!own) softmax(std::false_type{}, it);
       else softmax(std::true_type{}, it);
       bf16x8 pb[4];
       pack_p(pb);
@@ -490,18 +491,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
 
   if (j < TJ) {
     if (!acc_loaded) load_acc();                 // no prefix tile was walked (first segment)
-    if (PASS == 1) {
-      // leave the un-normalised state for the second pass
-      float* sp = a.st_acc + st_row * kD + 64 * hh;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const f32x4 v = {o[db][4 * i4], o[db][4 * i4 + 1], o[db][4 * i4 + 2], o[db][4 * i4 + 3]};
-          *reinterpret_cast<f32x4*>(sp + 16 * db + 4 * i4) = v;
-        }
-      if (hh == 0) { a.st_l[st_row] = l_run; a.st_m[st_row] = m_ref; }
-    } else {
+    {
       // normalise and scatter to the original row: lane holds dims 32*db + 8*(i/4) + 4*hh + i%4
       const float inv = 1.0f / l_run;
       uint16_t* orow = Oh + (int64_t)(nS + qoff) * a.os[2];
