@@ -275,12 +275,12 @@ def main():
         "plan_frac_of_hbm_peak": plan_bytes(w) / (plan_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "input_generation_s": t_gen,
         "roofline": {"bound": "mfma",
-                     "kernel": "s2o_attention_kernel<0> (fused)" if args.fused else "s2o_attention_kernel<2> (prefix walk)",
+                     "kernel": "s2o_attention_kernel (fused)" if args.fused else "s2o_prefix_kernel (prefix walk)",
                      "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": dom_tflops / PEAK_BF16_TFLOPS, "ms_per_launch": prefix_ms,
                      "flops_per_launch": dom_flops,
                      "traffic": None if args.fused else recorded_traffic(w.name, args.tau, w.BM,
-                                                                         "s2o_attention_kernel<2>")},
+                                                                         "s2o_prefix_kernel")},
         "cpu_baseline": cpu,
         "paper_context": "other hardware, context only: the paper reports 7.51x (7.53x in the text) attention speed-up over "
                          "FlashAttention-2 and 3.82x lower MSE at matched sparsity on 'NVIDIA GPUs' (Triton, 128x128 tiles, "

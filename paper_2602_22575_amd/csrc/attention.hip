@@ -12,8 +12,9 @@
 // per wavefront and is taken one tile late (the PV product of a tile waits for its vote).  The
 // dense intra-segment causal window (Pass-1) is run by the same loop before the prefix
 // walk, with identity indices and a per-element causal mask, so its state never leaves
-// registers.  (That is the single-launch form; with a state buffer the own-segment pass runs
-// as its own kernel, local.hip, and this kernel only walks the prefix.)
+// registers.  (That is the single-launch form, used when the caller gives no state buffer;
+// with one, the own-segment pass and the prefix walk run as kernels of their own, local.hip
+// and prefix.hip, which share this file's formulation.)
 //
 // MFMA formulation (v_mfma_f32_32x32x16_bf16), transposed so that a query row lives in
 // one lane pair and softmax statistics need a single cross-lane step:
@@ -43,7 +44,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kD = 128;          // head dim
 constexpr int kBN = 64;          // key tile
@@ -69,14 +69,10 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, t);
 }
 
-// PASS 0: everything in one launch (own-segment window, then the prefix walk).
-// PASS 2: Alg. 3 alone -- gathers the queries by Q_perm, resumes each row from the state
-//         (acc, l, m: the A, Lbuf, Mbuf buffers of the paper) that the own-segment pass
-//         (Alg. 2, local.hip) left in the state buffers, and walks the prefix.
-// Two launches cost a round trip of the fp32 state through HBM but halve the own-segment
-// work: a permuted query tile needs every own-segment key tile (with a per-element mask),
-// a tile in original order only those up to its diagonal.
-template <int PASS>
+// Everything in one launch: own-segment window, then the prefix walk.  (The two-launch form
+// costs a round trip of the fp32 state through HBM but halves the own-segment work: a
+// permuted query tile needs every own-segment key tile with a per-element mask, a tile in
+// original order only those up to its diagonal.)
 __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
@@ -154,8 +150,8 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   int wg_pmax = -1;
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) wg_pmax = max(wg_pmax, sflag[w]);
-  // own-segment key tiles this workgroup needs (none in the second pass of two)
-  const int nloc = PASS == 2 ? 0 : wg_pmax / kBN + 1;
+  // own-segment key tiles this workgroup needs
+  const int nloc = wg_pmax / kBN + 1;
   const int ntiles = nloc + nK;
 
   // ---- loader: wavefronts 0-3 move K, 4-7 move V, 4 groups of 4 rows each per tile; in a
@@ -241,26 +237,6 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
   int committed = 0, issued = 0;
   const float c2 = a.scale_log2e;
-  // state buffers: row (z, h, l) -> acc [128] fp32 in the accumulator's register order, l, m
-  const int64_t st_row = zh * a.L + nS + qoff;
-  // The statistics are needed by the first softmax; the accumulator only by the first PV
-  // product, which in the prefix walk runs one step late: its 512 bytes per row are
-  // requested after the first tile's scores have been issued and arrive behind them.
-  auto load_acc = [&] {
-    const float* sp = a.st_acc + st_row * kD + 64 * hh;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const f32x4 v = *reinterpret_cast<const f32x4*>(sp + 16 * db + 4 * i4);
-        o[db][4 * i4] = v[0]; o[db][4 * i4 + 1] = v[1]; o[db][4 * i4 + 2] = v[2]; o[db][4 * i4 + 3] = v[3];
-      }
-  };
-  bool acc_loaded = PASS != 2;
-  if (PASS == 2 && active) {
-    l_run = a.st_l[st_row];
-    m_ref = a.st_m[st_row];
-  }
 
   // values a tile's score step hands to its PV step
   f32x16 s[2];
@@ -389,7 +365,6 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
       else softmax(std::true_type{}, it);
       bf16x8 pb[4];
       pack_p(pb);
-      if (!acc_loaded) { load_acc(); acc_loaded = true; }
       rescale(alpha, grow);
       pv(it % 3, pb);
       l_run = prev + mass;
@@ -425,7 +400,6 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     // first prefix tile: scores only
     if (it + 1 < ntiles) load_tile(it + 1);
     qk(it & 1);
-    if (!acc_loaded) { load_acc(); acc_loaded = true; }
     softmax(std::false_type{}, it);
     publish(it);
     __syncthreads();
@@ -490,7 +464,6 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   }
 
   if (j < TJ) {
-    if (!acc_loaded) load_acc();                 // no prefix tile was walked (first segment)
     {
       // normalise and scatter to the original row: lane holds dims 32*db + 8*(i/4) + 4*hh + i%4
       const float inv = 1.0f / l_run;
@@ -518,16 +491,18 @@ size_t attention_state_bytes(int Z, int H, int L) {
 }
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
+  if (a.passes != 0) {                 // separate kernels through the state buffers
+    if (a.passes & 1) {
+      const hipError_t e = launch_local(a, stream);
+      if (e != hipSuccess) return e;
+    }
+    return (a.passes & 2) ? launch_prefix(a, stream) : hipSuccess;
+  }
   static std::mutex mu;
   static uint64_t done = 0;
   const hipError_t se = once_per_device(mu, done, [] {
-    const void* fns[2] = {reinterpret_cast<const void*>(&s2o_attention_kernel<0>),
-                          reinterpret_cast<const void*>(&s2o_attention_kernel<2>)};
-    for (const void* f : fns) {
-      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds);
-      if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&s2o_attention_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds);
   });
   if (se != hipSuccess) return se;
   const int TJ = a.S / a.BM;
@@ -535,16 +510,7 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
   const int JG = (TJ + tpw - 1) / tpw;
   const int64_t blocks = (int64_t)a.Z * a.H * a.N * JG;
   if (blocks <= 0 || blocks > 0x7fffffff) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)blocks), block(kThreads);
-  if (a.passes == 0) {
-    hipLaunchKernelGGL(s2o_attention_kernel<0>, grid, block, kAttnLds, stream, a);
-  } else {
-    if (a.passes & 1) {
-      const hipError_t e = launch_local(a, stream);
-      if (e != hipSuccess) return e;
-    }
-    if (a.passes & 2) hipLaunchKernelGGL(s2o_attention_kernel<2>, grid, block, kAttnLds, stream, a);
-  }
+  hipLaunchKernelGGL(s2o_attention_kernel, dim3((unsigned)blocks), dim3(kThreads), kAttnLds, stream, a);
   return hipGetLastError();
 }
 

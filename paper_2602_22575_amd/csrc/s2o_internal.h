@@ -69,5 +69,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t stream);
 // Alg. 2 alone (local.hip): own-segment pass in original query order into the state buffers
 hipError_t launch_local(const AttnArgs& a, hipStream_t stream);
+// Alg. 3 alone (prefix.hip): prefix walk in permuted query order from the state buffers
+hipError_t launch_prefix(const AttnArgs& a, hipStream_t stream);
 
 }  // namespace s2o
