@@ -44,6 +44,9 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, t);
 }
 
+// kNoStop: stop_mode 2 (every prefix tile folded in, the paper's kernel C) as an instantiation
+// of its own, so that neither loop's registers weigh on the other.
+template <bool kNoStop>
 __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
@@ -145,11 +148,13 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
     for (int gi = 0; gi < 4; ++gi) tokv[gi] = tokk[gi];
     load_index(t + 2);
   };
+  constexpr bool no_stop = kNoStop;        // no stop rule: PV follows its scores at once, V comes with K
   if (ntiles > 0) {
     load_index(0);
     load_k(0);
 #pragma unroll
     for (int gi = 0; gi < 4; ++gi) tokv[gi] = tokk[gi];
+    if (no_stop) load_v(0);
     load_index(1);
   }
 
@@ -307,16 +312,9 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   bf16x8 pb_pend[4];
   float alpha_pend = 1.f, l_save = 0.f, m_save = 0.f;
   bool grow_pend = false;
-  const bool no_stop = a.stop_mode == 2;
-  auto vote_flags = [&](int step) { return sflag + kWaves * (step & 1); };
-  auto publish = [&](int step) {        // after softmax of tile `step`: vote + speculative stats
-    const bool keep = no_stop || __builtin_amdgcn_ballot_w64(mass >= a.tau * prev) != 0ull;
-    if (lane == 0) vote_flags(step)[wave] = keep ? 1 : 0;
-    l_save = l_run; m_save = m_ref;
-    l_run = prev + mass; m_ref = m_use;
-    alpha_pend = alpha; grow_pend = grow;
+  auto pack_p = [&] {                   // P^T fragments (bf16) for the four 16-key contraction steps
 #pragma unroll
-    for (int st = 0; st < 4; ++st) {    // P^T fragments (bf16) for the four 16-key contraction steps
+    for (int st = 0; st < 4; ++st) {
       const int nb = st >> 1, k2 = st & 1;
       u32x4 w;
 #pragma unroll
@@ -324,6 +322,15 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
         w[q] = pack_bf16x2(s[nb][8 * k2 + 2 * q], s[nb][8 * k2 + 2 * q + 1]);
       pb_pend[st] = __builtin_bit_cast(bf16x8, w);
     }
+  };
+  auto vote_flags = [&](int step) { return sflag + kWaves * (step & 1); };
+  auto publish = [&](int step) {        // after softmax of tile `step`: vote + speculative stats
+    const bool keep = __builtin_amdgcn_ballot_w64(mass >= a.tau * prev) != 0ull;
+    if (lane == 0) vote_flags(step)[wave] = keep ? 1 : 0;
+    l_save = l_run; m_save = m_ref;
+    l_run = prev + mass; m_ref = m_use;
+    alpha_pend = alpha; grow_pend = grow;
+    pack_p();
     ++issued;
   };
   auto tile_votes = [&](const int* vf) {
@@ -339,7 +346,31 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   };
 
   bool acc_loaded = false;
-  if (ntiles > 0) {
+  if (no_stop && ntiles > 0) {
+    // ---- every prefix tile is folded in (no votes, nothing deferred): step k reads K(k) and
+    // V(k) while K(k+1) and V(k+1) arrive
+    __syncthreads();                            // K and V tile 0 have landed
+    for (int it = 0; it < ntiles; ++it) {
+      if (it + 1 < ntiles) {
+        load_k(it + 1);
+#pragma unroll
+        for (int gi = 0; gi < 4; ++gi) tokv[gi] = tokk[gi];
+        load_v(it + 1);
+        load_index(it + 2);
+      }
+      if (active) {
+        qk(it & 1);
+        if (!acc_loaded) { load_acc(); acc_loaded = true; }
+        softmax();
+        pack_p();
+        rescale(alpha, grow);
+        pv(it & 1, pb_pend);
+        l_run = prev + mass; m_ref = m_use;
+        ++committed; ++issued;
+      }
+      __syncthreads();
+    }
+  } else if (ntiles > 0) {
     __syncthreads();                            // K tile 0 has landed
     int it = 0;
     bool wg_done = false;
@@ -355,7 +386,6 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
       for (it = 1; it < ntiles; ++it) {
         const int* vf = vote_flags(it - 1);
         const int votes = tile_votes(vf);
-        qk(it & 1);                             // issued before the vote is looked at
         if (votes == 0) {
           const int any = wg_votes(vf);
           if (a.stop_mode == 0) {
@@ -369,6 +399,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
           wg_done = any == 0;
           break;
         }
+        qk(it & 1);
         load_step(it);
         rescale(alpha_pend, grow_pend);
         pv((it - 1) & 1, pb_pend);
@@ -428,8 +459,13 @@ hipError_t launch_prefix(const AttnArgs& a, hipStream_t stream) {
   static std::mutex mu;
   static uint64_t done = 0;
   const hipError_t se = once_per_device(mu, done, [] {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&s2o_prefix_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPrefixLds);
+    const void* fns[2] = {reinterpret_cast<const void*>(&s2o_prefix_kernel<false>),
+                          reinterpret_cast<const void*>(&s2o_prefix_kernel<true>)};
+    for (const void* f : fns) {
+      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPrefixLds);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
   });
   if (se != hipSuccess) return se;
   const int TJ = a.S / a.BM;
@@ -437,7 +473,10 @@ hipError_t launch_prefix(const AttnArgs& a, hipStream_t stream) {
   const int JG = (TJ + tpw - 1) / tpw;
   const int64_t blocks = (int64_t)a.Z * a.H * a.N * JG;
   if (blocks <= 0 || blocks > 0x7fffffff) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(s2o_prefix_kernel, dim3((unsigned)blocks), dim3(kThreads), kPrefixLds, stream, a);
+  if (a.stop_mode == 2)
+    hipLaunchKernelGGL(s2o_prefix_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), kPrefixLds, stream, a);
+  else
+    hipLaunchKernelGGL(s2o_prefix_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), kPrefixLds, stream, a);
   return hipGetLastError();
 }
 
