@@ -28,7 +28,9 @@
 // rows) in LDS, written there directly by global_load_lds (no staging registers): a
 // wavefront instruction deposits 4 gathered rows as 1 KB, lane l at byte 16*l, so rows
 // cannot be padded; bank conflicts are avoided by an XOR swizzle instead (lane l fetches
-// chunk (l%16) ^ swz(row) of its row, swz(r) = 2*(r%8) + (r/8)%2).
+// chunk (l%16) ^ swz(row) of its row, swz(r) = 4*(r%4) + 2*((r/4)%2) + (r/8)%2: the 16 rows
+// a 16-byte K read touches land on 16 different chunks, and the 4 rows x 64 bytes that half
+// a wavefront touches in a transposing V read land on the four 16-bank groups).
 // The K operand is a plain 16-byte read of a row; the V^T operand is read
 // with the transposing LDS load ds_read_b64_tr_b16: within each group of 16 lanes, lane i
 // receives element (i % 4) of the four 8-byte rows pointed to by lanes i/4, 4 + i/4, 8 + i/4
@@ -156,7 +158,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
 
   // ---- loader: wavefronts 0-3 move K, 4-7 move V, 4 groups of 4 rows each per tile; in a
   // group lane l moves one 16-byte chunk of row 4*group + l/16 straight into LDS
-  auto swz = [](int r) { return ((r & 7) << 1) | ((r >> 3) & 1); };
+  auto swz = [](int r) { return ((r & 3) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1); };
   const bool loads_v = wave >= 4;
   const uint16_t* src = loads_v ? Vh : Kh;
   const int64_t src_stride = loads_v ? a.vs[2] : a.ks[2];

@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_local_kernel(const AttnArgs a
 
   // ---- loader: every wavefront moves 16 rows of K and 16 rows of V per tile, 4 rows per
   // instruction (lane l: one 16-byte chunk of row 4*group + l/16, straight into LDS)
-  auto swz = [](int r) { return ((r & 7) << 1) | ((r >> 3) & 1); };
+  auto swz = [](int r) { return ((r & 3) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1); };
   const uint32_t k_stride_bytes = (uint32_t)(a.ks[2] * 2), v_stride_bytes = (uint32_t)(a.vs[2] * 2);
   int goff[4];
 #pragma unroll

@@ -110,7 +110,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   // instruction (lane l: one 16-byte chunk of row 4*group + l/16, straight into LDS).  The
   // token indices are read two tiles ahead of the K fetch that uses them, so a fetch never
   // waits for its own index loads; the V fetch of a tile reuses its K fetch's indices.
-  auto swz = [](int r) { return ((r & 7) << 1) | ((r >> 3) & 1); };
+  auto swz = [](int r) { return ((r & 3) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1); };
   const uint32_t k_stride_bytes = (uint32_t)(a.ks[2] * 2), v_stride_bytes = (uint32_t)(a.vs[2] * 2);
   int goff[4];
 #pragma unroll
