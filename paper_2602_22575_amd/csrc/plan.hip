@@ -199,7 +199,7 @@ __global__ __launch_bounds__(256) void pool_sq_sort_kernel(PlanArgs a, Scratch s
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int n2 = next_pow2(a.S);
   uint64_t* keys = reinterpret_cast<uint64_t*>(smem);               // [n2]
-  float* red = reinterpret_cast<float*>(smem + (size_t)n2 * 8);     // [16][128]
+  float* red = reinterpret_cast<float*>(smem + (size_t)n2 * 8);     // [4 wavefronts][128]
 
   const int G = a.H / a.Hkv;
   const int64_t row_id = blockIdx.x;                                // (z*H + h)*N + n
@@ -245,14 +245,19 @@ __global__ __launch_bounds__(256) void pool_sq_sort_kernel(PlanArgs a, Scratch s
     }
   }
   for (int i = a.S + tid; i < n2; i += 256) keys[i] = ~0ull;
-  // ---- q_mean
+  // ---- q_mean: column sums over the wavefront's four row groups, then over the wavefronts
 #pragma unroll
-  for (int j = 0; j < 8; ++j) red[r * kD + 8 * c + j] = acc[j];
+  for (int j = 0; j < 8; ++j) {
+    acc[j] += __shfl_xor(acc[j], 16);
+    acc[j] += __shfl_xor(acc[j], 32);
+  }
+  if ((tid & 63) < 16) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) red[(tid >> 6) * kD + 8 * c + j] = acc[j];
+  }
   __syncthreads();
   if (tid < kD) {
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) s += red[i * kD + tid];
+    float s = (red[tid] + red[kD + tid]) + (red[2 * kD + tid] + red[3 * kD + tid]);
     s *= 1.0f / (float)a.S;
     sc.qmean[row_id * kD + tid] = s;
     if (a.q_mean) a.q_mean[row_id * kD + tid] = s;
@@ -442,6 +447,12 @@ __global__ __launch_bounds__(256) void count_kernel(PlanArgs a, Scratch sc) {
   if (t_begin >= lim) return;
   const int t_end = min(t_begin + sc.cell, lim);
   const int tid = threadIdx.x;
+  // four consecutive scores per thread, requested before the splitters are staged (cells and
+  // prefix lengths are multiples of 4 tokens and rows start 16-byte aligned)
+  const float* sk = (a.s_k ? a.s_k : sc.sk) + row_base(a, row_id);
+  const int t0 = t_begin + 4 * tid;
+  f32x4 sv4 = {0.f, 0.f, 0.f, 0.f};
+  if (t0 < t_end) sv4 = *reinterpret_cast<const f32x4*>(sk + t0);
   if (tid < kNBMax) {
     spl[tid] = sc.splitters[row_id * kNBMax + tid];
     cnt[tid] = 0u;
@@ -450,8 +461,10 @@ __global__ __launch_bounds__(256) void count_kernel(PlanArgs a, Scratch sc) {
   float top[7];
 #pragma unroll
   for (int k = 0; k < 7; ++k) top[k] = spl[8 * k + 7];
-  const float* sk = (a.s_k ? a.s_k : sc.sk) + row_base(a, row_id);
-  for (int t = t_begin + tid; t < t_end; t += 256) atomicAdd(&cnt[bucket_of_score(spl, top, sk[t])], 1u);
+  if (t0 < t_end) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) atomicAdd(&cnt[bucket_of_score(spl, top, sv4[e])], 1u);
+  }
   __syncthreads();
   if (tid < kNBMax) sc.chist[(row_id * sc.maxch + cellno) * kNBMax + tid] = (uint16_t)cnt[tid];
 }
@@ -475,6 +488,11 @@ __global__ __launch_bounds__(256) void scatter_kernel(PlanArgs a, Scratch sc) {
   const int t_end = min(t_begin + sc.cell, lim);
   const int tid = threadIdx.x;
   const int64_t cell = (row_id * sc.maxch + cellno) * kNBMax;
+  const int64_t base = row_base(a, row_id);
+  const float* sk = (a.s_k ? a.s_k : sc.sk) + base;
+  const int t0 = t_begin + 4 * tid;             // four consecutive scores per thread, as in the count
+  f32x4 sv4 = {0.f, 0.f, 0.f, 0.f};
+  if (t0 < t_end) sv4 = *reinterpret_cast<const f32x4*>(sk + t0);
   if (tid < kNBMax) {                           // one wavefront: exclusive scan of the cell's counts
     spl[tid] = sc.splitters[row_id * kNBMax + tid];
     const uint32_t v = sc.chist[cell + tid];
@@ -491,17 +509,18 @@ __global__ __launch_bounds__(256) void scatter_kernel(PlanArgs a, Scratch sc) {
   float top[7];
 #pragma unroll
   for (int k = 0; k < 7; ++k) top[k] = spl[8 * k + 7];
-  const int64_t base = row_base(a, row_id);
-  const float* sk = (a.s_k ? a.s_k : sc.sk) + base;
-  for (int t = t_begin + tid; t < t_end; t += 256) {
-    const float sv = sk[t];
-    const int bk = bucket_of_score(spl, top, sv);
-    const uint32_t slot = atomicAdd(&cur[bk], 1u);
-    if (slot < (uint32_t)kCellMax) {
-      stage[slot] = sort_key(sv, (uint32_t)t);
-      sdst[slot] = delta[bk] + slot;
-    } else {
-      sc.counters[2] = 1u;
+  if (t0 < t_end) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float sv = sv4[e];
+      const int bk = bucket_of_score(spl, top, sv);
+      const uint32_t slot = atomicAdd(&cur[bk], 1u);
+      if (slot < (uint32_t)kCellMax) {
+        stage[slot] = sort_key(sv, (uint32_t)(t0 + e));
+        sdst[slot] = delta[bk] + slot;
+      } else {
+        sc.counters[2] = 1u;
+      }
     }
   }
   __syncthreads();
@@ -606,7 +625,7 @@ __global__ __launch_bounds__(4 * kNBMax) void scan_kernel(PlanArgs a, Scratch sc
 constexpr int kSortThreads = 1024;
 constexpr int kPerThread = kSubBuckets / kSortThreads;   // sub-bucket counters scanned per thread
 
-__global__ __launch_bounds__(kSortThreads) void span_sort_kernel(PlanArgs a, Scratch sc) {
+__global__ __launch_bounds__(kSortThreads, 8) void span_sort_kernel(PlanArgs a, Scratch sc) {
   __shared__ uint64_t keys[kSpanCap];
   __shared__ uint16_t grp[kSpanCap];
   __shared__ uint32_t start[kSubBuckets + 1];
@@ -615,20 +634,40 @@ __global__ __launch_bounds__(kSortThreads) void span_sort_kernel(PlanArgs a, Scr
   __shared__ uint32_t red[3];          // min / max of the ordered score bits, fullest sub-bucket
   const int tid = threadIdx.x;
   const uint32_t nspans = min(sc.counters[0], (uint32_t)sc.max_spans);
+  // A workgroup sorts spans blockIdx.x, blockIdx.x + gridDim.x, ...; the pairs of the next span
+  // are requested (into registers) while the current one is sorted.
+  constexpr int kPerLoad = kSpanCap / kSortThreads;
+  int4 sp = make_int4(0, 0, 0, 0);
+  uint64_t held[kPerLoad];
+  auto fetch = [&](uint32_t w) {
+    sp = sc.spans[w];
+    const uint64_t* src = sc.pairs + row_base(a, sp.x) + sp.y;
+    const int n = sp.z - sp.y;
+#pragma unroll
+    for (int e = 0; e < kPerLoad; ++e) {
+      const int i = tid + e * kSortThreads;
+      held[e] = i < n ? src[i] : 0ull;
+    }
+  };
+  if (blockIdx.x < nspans) fetch(blockIdx.x);
   for (uint32_t w = blockIdx.x; w < nspans; w += gridDim.x) {
-    const int4 sp = sc.spans[w];
     const int64_t base = row_base(a, sp.x) + sp.y;
     const int len = sp.z - sp.y;
     if (tid == 0) { red[0] = 0xffffffffu; red[1] = 0u; red[2] = 0u; }
     for (int i = tid; i < kSubBuckets; i += kSortThreads) fill[i] = 0;
     __syncthreads();
     uint32_t lo = 0xffffffffu, hi = 0u;
-    for (int i = tid; i < len; i += kSortThreads) {
-      const uint64_t k = sc.pairs[base + i];
-      keys[i] = k;
-      const uint32_t o = ~(uint32_t)(k >> 32);   // ordered score bits (ascending = ascending score)
-      lo = min(lo, o); hi = max(hi, o);
+#pragma unroll
+    for (int e = 0; e < kPerLoad; ++e) {
+      const int i = tid + e * kSortThreads;
+      if (i < len) {
+        const uint64_t k = held[e];
+        keys[i] = k;
+        const uint32_t o = ~(uint32_t)(k >> 32);   // ordered score bits (ascending = ascending score)
+        lo = min(lo, o); hi = max(hi, o);
+      }
     }
+    if (w + gridDim.x < nspans) fetch(w + gridDim.x);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
       lo = min(lo, (uint32_t)__shfl_xor((int)lo, o));
@@ -771,7 +810,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
     static uint64_t done = 0;
     const hipError_t se = once_per_device(mu, done, [] {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pool_sq_sort_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8 + 16 * kD * 4);
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 8 + 4 * kD * 4);
       if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&splitter_kernel),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSplitterLdsMax);
       return e;
@@ -784,7 +823,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
   {
     int n2 = 1;
     while (n2 < a.S) n2 <<= 1;
-    const size_t lds = (size_t)n2 * 8 + 16 * kD * 4;
+    const size_t lds = (size_t)n2 * 8 + 4 * kD * 4;
     hipLaunchKernelGGL(pool_sq_sort_kernel, dim3((unsigned)rows), dim3(256), lds, stream, a, sc);
   }
   if (a.N > 1) {
