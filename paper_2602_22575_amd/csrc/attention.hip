@@ -14,61 +14,30 @@
 // walk, with identity indices and a per-element causal mask, so its state never leaves
 // registers.  (That is the single-launch form, used when the caller gives no state buffer;
 // with one, the own-segment pass and the prefix walk run as kernels of their own, local.hip
-// and prefix.hip, which share this file's formulation.)
+// and prefix.hip.)
 //
-// MFMA formulation (v_mfma_f32_32x32x16_bf16), transposed so that a query row lives in
-// one lane pair and softmax statistics need a single cross-lane step:
-//   S^T[n, m] = sum_d K[n, d] Q[m, d]        A = K tile rows from LDS, B = Q from registers
-//   O^T[d, m] = sum_n V^T[d, n] P^T[n, m]    A = V^T from LDS,        B = P from the S^T
-//                                            accumulators (no data movement)
-// Lane l = (m = l % 32, hh = l / 32).  A 32x32 accumulator block holds, in register i of lane
-// l, the element [row 8*(i/4) + 4*hh + i%4][column m].  The B operand of the PV product takes
-// registers 8*kk..8*kk+7 of an S^T block as its 8 contraction slots, so slot (hh, jj) is key
-// 16*kk + 8*(jj/4) + 4*hh + jj%4 of the 32-key block.  K and V tiles sit row-major (token
-// rows) in LDS, written there directly by global_load_lds (no staging registers): a
-// wavefront instruction deposits 4 gathered rows as 1 KB, lane l at byte 16*l, so rows
-// cannot be padded; bank conflicts are avoided by an XOR swizzle instead (lane l fetches
-// chunk (l%16) ^ swz(row) of its row, swz(r) = 4*(r%4) + 2*((r/4)%2) + (r/8)%2: the 16 rows
-// a 16-byte K read touches land on 16 different chunks, and the 4 rows x 64 bytes that half
-// a wavefront touches in a transposing V read land on the four 16-bank groups).
-// The K operand is a plain 16-byte read of a row; the V^T operand is read
-// with the transposing LDS load ds_read_b64_tr_b16: within each group of 16 lanes, lane i
-// receives element (i % 4) of the four 8-byte rows pointed to by lanes i/4, 4 + i/4, 8 + i/4
-// and 12 + i/4, so pointing lane r of a group at (key slot r/4, dims 4*(r%4)..+3) hands every
-// lane the four keys of its contraction slots at its own head dimension.
-#include <type_traits>
-
+// MFMA formulation, LDS layouts and the base-2 online softmax with lazy rescaling are in
+// attn_tile.h.
+#include "attn_tile.h"
 #include "s2o_internal.h"
 
 namespace s2o {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+namespace {
 
-constexpr int kD = 128;          // head dim
-constexpr int kBN = 64;          // key tile
-constexpr int kRowsPerWave = 32; // query rows of one wavefront
+using namespace tile;
+
 constexpr int kWaves = 8;        // a query tile of B_M rows is B_M/32 wavefronts: 4 tiles of 64
                                  // rows or 2 tiles of 128 rows per workgroup
 constexpr int kThreads = 64 * kWaves;
-constexpr int kRowElems = kD;    // K and V rows sit unpadded in LDS (256 B); the sixteen 16-byte
-                                 // chunks of row r are stored at slot (chunk ^ swz(r)) instead
-constexpr int kKsElems = kBN * kRowElems;
-constexpr int kVtElems = kBN * kRowElems;
+constexpr int kKsElems = kTileElems;
+constexpr int kVtElems = kTileElems;
 constexpr size_t kAttnLds = (size_t)(2 * kKsElems + 3 * kVtElems) * 2 + 256;
 
 __device__ inline int wave_max_i32(int v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o));
   return v;
-}
-
-__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  bf16x2 t = {(__bf16)lo, (__bf16)hi};
-  return __builtin_bit_cast(uint32_t, t);
 }
 
 // Everything in one launch: own-segment window, then the prefix walk.  (The two-launch form
@@ -90,32 +59,9 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   const int TJ = a.S / BM;                               // query tiles per segment
   const int JG = (TJ + tpw - 1) / tpw;                   // workgroups per (z,h,n)
 
-  // ---- block -> (z, h, n, jg).  Longest prefixes first.  Consecutive block ids are dealt
-  // round-robin to the 8 XCDs, each with its own L2: the JG workgroups of one (z, h, n) walk
-  // the same KV_perm row at about the same time, so they are given ids that land on one XCD
-  // (their gathered K/V tiles then hit in that L2), while the XCD of a head rotates with the
-  // segment so that heads that stop early and heads that never stop mix evenly on every XCD.
-  int z, h, n, jg;
-  {
-    const int ZH = a.Z * a.H;
-    const int b = blockIdx.x;
-    int zh_, nr;
-    if (ZH % 8 == 0) {
-      const int xcd = b & 7, idx = b >> 3, per = ZH / 8;
-      jg = idx % JG;
-      const int unit = idx / JG;
-      nr = unit / per;
-      zh_ = ((xcd - nr) & 7) + 8 * (unit % per);
-    } else {
-      jg = b % JG;
-      const int unit = b / JG;
-      nr = unit / ZH;
-      zh_ = unit % ZH;
-    }
-    n = a.N - 1 - nr;
-    z = zh_ / a.H;
-    h = zh_ % a.H;
-  }
+  int zh_, nr, jg;
+  map_block(blockIdx.x, a.Z * a.H, JG, zh_, nr, jg);
+  const int n = a.N - 1 - nr, z = zh_ / a.H, h = zh_ % a.H;
   const int g = h / G;
   const uint16_t* Qh = a.Q + z * a.qs[0] + h * a.qs[1];
   const uint16_t* Kh = a.K + z * a.ks[0] + g * a.ks[1];
@@ -141,10 +87,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     const int r = min(j, TJ - 1) * BM + kRowsPerWave * part + m_;
     qoff = a.use_q_perm ? a.q_perm[(zh * a.N + n) * a.S + r] : r;
     qoff = min(max(qoff, 0), a.S - 1);
-    const uint16_t* qrow = Qh + (int64_t)(nS + qoff) * a.qs[2];
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk)
-      qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * hh);
+    load_q(Qh + (int64_t)(nS + qoff) * a.qs[2], hh, qf);
   }
   const int wave_pmax = active ? wave_max_i32(qoff) : -1;
   if (lane == 0) sflag[wave] = wave_pmax;
@@ -156,14 +99,10 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   const int nloc = wg_pmax / kBN + 1;
   const int ntiles = nloc + nK;
 
-  // ---- loader: wavefronts 0-3 move K, 4-7 move V, 4 groups of 4 rows each per tile; in a
-  // group lane l moves one 16-byte chunk of row 4*group + l/16 straight into LDS
-  auto swz = [](int r) { return ((r & 3) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1); };
+  // ---- loader: wavefronts 0-3 move K, 4-7 move V, 4 groups of 4 rows each per tile
   const bool loads_v = wave >= 4;
   const uint16_t* src = loads_v ? Vh : Kh;
   const int64_t src_stride = loads_v ? a.vs[2] : a.ks[2];
-  typedef __attribute__((address_space(1))) void gvoid;
-  typedef __attribute__((address_space(3))) void lvoid;
   // token indices of the tile after the one being fetched are read one step ahead, so that a
   // fetch never waits for its own index loads
   int tokn[4];
@@ -183,167 +122,32 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   const char* gbase[4];                 // per group: head base + this lane's (swizzled) chunk
 #pragma unroll
   for (int gi = 0; gi < 4; ++gi)
-    gbase[gi] = reinterpret_cast<const char*>(src) + 16 * ((lane & 15) ^ swz(16 * (wave & 3) + 4 * gi + (lane >> 4)));
+    gbase[gi] = reinterpret_cast<const char*>(src) + load_chunk_offset(lane, 16 * (wave & 3) + 4 * gi);
   auto load_tile = [&](int it) {       // K tiles alternate between 2 buffers, V tiles between 3
     uint16_t* dst = loads_v ? Vt + (it % 3) * kVtElems : Ks + (it & 1) * kKsElems;
 #pragma unroll
     for (int gi = 0; gi < 4; ++gi) {
       const uint32_t tok = (uint32_t)min(max(tokn[gi], 0), a.L - 1);
-      const char* gp = gbase[gi] + (uint64_t)tok * stride_bytes;   // one 64-bit multiply-add
-      __builtin_amdgcn_global_load_lds((const gvoid*)gp, (lvoid*)(dst + (16 * (wave & 3) + 4 * gi) * kRowElems),
-                                       16, 0, 0);
+      load_rows_to_lds(gbase[gi] + (uint64_t)tok * stride_bytes,   // one 64-bit multiply-add
+                       dst + (16 * (wave & 3) + 4 * gi) * kRowElems);
     }
     load_index(it + 1);
   };
-  // K operand: row 32*nb + m_, chunk 2*kk + hh -> per-lane byte offsets for the 8 steps
-  int koff[8];
-#pragma unroll
-  for (int kk = 0; kk < 8; ++kk) koff[kk] = m_ * kRowElems + 8 * ((2 * kk + hh) ^ swz(m_));
-  // transposing read of 4 keys x this lane's dimension: lane (group g16 = lane/16, r = lane%16)
-  // points at key slot r/4 (+ 4 for the upper lane half), dims 16*(g16&1) + 4*(r%4); the row's
-  // swizzle depends on the lane and on which 8-key half (a) of the 16-key step is read
-  typedef short i16x4 __attribute__((ext_vector_type(4)));
-  typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
-  int voff[4][2];
-  {
-    const int rl = ((lane & 15) >> 2) + 4 * (lane >> 5);          // row inside the 8-key half
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int a8 = 0; a8 < 2; ++a8) {
-        const int chunk = 4 * db + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-        voff[db][a8] = (rl + 8 * a8) * kRowElems + 8 * (chunk ^ swz(rl + 8 * a8)) + 4 * (lane & 1);
-      }
-  }
-  auto read_vt = [&](const uint16_t* vt, int key0, int db) -> bf16x8 {
-    // contraction slots (hh, jj): jj < 4 -> keys key0 + 4*hh + jj, jj >= 4 -> keys key0 + 8 + 4*hh + jj - 4
-    const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vt + key0 * kRowElems + voff[db][0]));
-    const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vt + key0 * kRowElems + voff[db][1]));
-    u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-    u32x4 w = {l2.x, l2.y, h2.x, h2.y};
-    return __builtin_bit_cast(bf16x8, w);
-  };
+  Operands op;
+  op.init(lane);
 
-  // ---- online-softmax state and output accumulator O^T[d-block].  Logits are kept in
-  // base-2 units (raw score * softmax_scale * log2 e).  m_ref is the reference maximum the
-  // accumulated terms are expressed in; it follows the true running maximum lazily: terms
-  // are only rescaled when the maximum has grown by more than kLazy (2^8), so that in the
-  // common case a tile costs no pass over the accumulator.  Any reference gives the same
-  // result; tile masses and the stop test are ratios in one common reference.
-  constexpr float kLazy = 8.0f;
+  // ---- online-softmax state and output accumulator O^T[d-block]
   float m_ref = -INFINITY, l_run = 0.f;
   f32x16 o[4];
-#pragma unroll
-  for (int db = 0; db < 4; ++db)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+  zero_acc(o);
   int committed = 0, issued = 0;
   const float c2 = a.scale_log2e;
 
   // values a tile's score step hands to its PV step
   f32x16 s[2];
-  float alpha, mass, prev, m_use;
-  bool grow;
-
-  // S^T = K Q^T for key tile buffer kbuf
-  auto qk = [&](int kbuf) {
-    const uint16_t* ks = Ks + kbuf * kKsElems;
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[nb][i] = 0.f;
-    // K fragments are fetched from LDS two contraction steps ahead of the MFMA that uses them
-    bf16x8 ka[3][2];
-#pragma unroll
-    for (int pre = 0; pre < 2; ++pre)
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-        ka[pre][nb] = *reinterpret_cast<const bf16x8*>(ks + 32 * nb * kRowElems + koff[pre]);
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      if (kk + 2 < 8) {
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-          ka[(kk + 2) % 3][nb] = *reinterpret_cast<const bf16x8*>(ks + 32 * nb * kRowElems + koff[kk + 2]);
-      }
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-        s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk % 3][nb], qf[kk], s[nb], 0, 0, 0);
-    }
-  };
-  // softmax numerators (left in s) and the row statistics of the tile
-  auto softmax = [&](auto local_tag, int it) {
-    constexpr bool kLocal = decltype(local_tag)::value;
-    float mx = -INFINITY;
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        if (kLocal) {
-          const int kpos = it * kBN + 32 * nb + 8 * (i >> 2) + 4 * hh + (i & 3);
-          if (kpos > qoff) s[nb][i] = -INFINITY;     // CausalMask
-        }
-        mx = fmaxf(mx, s[nb][i]);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32)) * c2;
-    grow = mx > m_ref + kLazy;
-    m_use = grow ? mx : m_ref;
-    float sum = 0.f;
-    const float neg = -m_use;
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float pe = __builtin_amdgcn_exp2f(fmaf(s[nb][i], c2, neg));
-        s[nb][i] = pe;
-        sum += pe;
-      }
-    sum += __shfl_xor(sum, 32);
-    mass = sum;
-    alpha = grow ? __builtin_amdgcn_exp2f(m_ref - m_use) : 1.0f;
-    prev = l_run * alpha;
-  };
-  // P^T fragments (bf16) for the four 16-key contraction steps
-  auto pack_p = [&](bf16x8 (&pb)[4]) {
-#pragma unroll
-    for (int st = 0; st < 4; ++st) {
-      const int nb = st >> 1, k2 = st & 1;
-      u32x4 w;
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        w[q] = pack_bf16x2(s[nb][8 * k2 + 2 * q], s[nb][8 * k2 + 2 * q + 1]);
-      pb[st] = __builtin_bit_cast(bf16x8, w);
-    }
-  };
-  // rare: move the accumulator to a new reference maximum (O^T *= alpha)
-  auto rescale = [&](float al, bool gr) {
-    if (__builtin_amdgcn_ballot_w64(gr) != 0ull) {
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][i] *= al;
-    }
-  };
-  // O^T += V^T P^T with the V tile in buffer vbuf
-  auto pv = [&](int vbuf, const bf16x8 (&pb)[4]) {
-    const uint16_t* vt = Vt + vbuf * kVtElems;
-    // V^T fragments are fetched one contraction step (4 blocks of 32 dims) ahead
-    bf16x8 va[2][4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-      va[0][db] = read_vt(vt, 0, db);
-#pragma unroll
-    for (int st = 0; st < 4; ++st) {
-      if (st + 1 < 4) {
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-          va[(st + 1) & 1][db] = read_vt(vt, 16 * (st + 1), db);
-      }
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[st & 1][db], pb[st], o[db], 0, 0, 0);
-    }
-  };
+  TileStats ts;
+  auto qk = [&](int kbuf) { qk_tile(Ks + kbuf * kKsElems, op, qf, s); };
+  auto pv = [&](int vbuf, const bf16x8 (&pb)[4]) { pv_tile(Vt + vbuf * kVtElems, op, pb, o); };
 
   load_index(0);
   load_tile(0);
@@ -363,14 +167,14 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
       qk(it & 1);
       // own-segment tiles always carry the causal mask: the rows of a permuted query tile are
       // scattered over the segment
-      if (!own) softmax(std::false_type{}, it);
-      else softmax(std::true_type{}, it);
+      ts = own ? softmax_tile<true>(s, c2, m_ref, l_run, it * kBN, qoff, hh)
+               : softmax_tile<false>(s, c2, m_ref, l_run, 0, 0, hh);
       bf16x8 pb[4];
-      pack_p(pb);
-      rescale(alpha, grow);
+      pack_p(s, pb);
+      rescale(o, ts.alpha, ts.grow);
       pv(it % 3, pb);
-      l_run = prev + mass;
-      m_ref = m_use;
+      l_run = ts.prev + ts.mass;
+      m_ref = ts.m_use;
       if (!own) { ++committed; ++issued; }
     }
     __syncthreads();
@@ -388,12 +192,12 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
   bool grow_pend = false;
   auto vote_flags = [&](int step) { return sflag + 8 + 8 * (step & 1); };
   auto publish = [&](int step) {        // after softmax of tile `step`: vote + speculative stats
-    const bool keep = __builtin_amdgcn_ballot_w64(mass >= a.tau * prev) != 0ull;
+    const bool keep = __builtin_amdgcn_ballot_w64(ts.mass >= a.tau * ts.prev) != 0ull;
     if (lane == 0) vote_flags(step)[wave] = keep ? 1 : 0;
     l_save = l_run; m_save = m_ref;
-    l_run = prev + mass; m_ref = m_use;
-    alpha_pend = alpha; grow_pend = grow;
-    pack_p(pb_pend);
+    l_run = ts.prev + ts.mass; m_ref = ts.m_use;
+    alpha_pend = ts.alpha; grow_pend = ts.grow;
+    pack_p(s, pb_pend);
     pending = true;
     ++issued;
   };
@@ -402,7 +206,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     // first prefix tile: scores only
     if (it + 1 < ntiles) load_tile(it + 1);
     qk(it & 1);
-    softmax(std::false_type{}, it);
+    ts = softmax_tile<false>(s, c2, m_ref, l_run, 0, 0, hh);
     publish(it);
     __syncthreads();
     ++it;
@@ -418,7 +222,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
         if (a.stop_mode == 0) {
           l_run = l_save; m_ref = m_save;
         } else {
-          rescale(alpha_pend, grow_pend);
+          rescale(o, alpha_pend, grow_pend);
           pv((it - 1) % 3, pb_pend);
           ++committed;
         }
@@ -427,10 +231,10 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
         break;
       }
       if (it + 1 < ntiles) load_tile(it + 1);
-      rescale(alpha_pend, grow_pend);
+      rescale(o, alpha_pend, grow_pend);
       pv((it - 1) % 3, pb_pend);
       ++committed;
-      softmax(std::false_type{}, it);
+      ts = softmax_tile<false>(s, c2, m_ref, l_run, 0, 0, hh);
       publish(it);
       __syncthreads();
     }
@@ -442,7 +246,7 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
       if (stop && a.stop_mode == 0) {
         l_run = l_save; m_ref = m_save;
       } else {
-        rescale(alpha_pend, grow_pend);
+        rescale(o, alpha_pend, grow_pend);
         pv((ntiles - 1) % 3, pb_pend);
         ++committed;
       }
@@ -467,18 +271,8 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
 
   if (j < TJ) {
     {
-      // normalise and scatter to the original row: lane holds dims 32*db + 8*(i/4) + 4*hh + i%4
-      const float inv = 1.0f / l_run;
-      uint16_t* orow = Oh + (int64_t)(nS + qoff) * a.os[2];
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          u32x2 w;
-          w.x = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
-          w.y = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
-          *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * i4 + 4 * hh) = w;
-        }
+      // normalise and scatter to the original row
+      store_o(Oh + (int64_t)(nS + qoff) * a.os[2], hh, o, 1.0f / l_run);
       if (lane == 0 && part == 0) {
         const int64_t ci = zh * (a.L / BM) + (int64_t)n * TJ + j;
         if (a.computed) a.computed[ci] = committed;
@@ -487,6 +281,8 @@ __global__ __launch_bounds__(kThreads, 1) void s2o_attention_kernel(const AttnAr
     }
   }
 }
+
+}  // namespace
 
 size_t attention_state_bytes(int Z, int H, int L) {
   return (size_t)Z * H * L * (kD + 2) * sizeof(float);

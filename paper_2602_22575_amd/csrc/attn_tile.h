@@ -1,0 +1,294 @@
+// Per-wavefront building blocks shared by the three S2O attention kernels for gfx950
+// (attention.hip: both passes in one launch; local.hip: own-segment pass, paper Alg. 2;
+// prefix.hip: prefix walk, paper Alg. 3): one wavefront = 32 query rows against one
+// 64-token key tile staged in LDS.
+//
+// MFMA formulation (v_mfma_f32_32x32x16_bf16), transposed so that a query row lives in one
+// lane pair and softmax statistics need a single cross-lane step:
+//   S^T[n, m] = sum_d K[n, d] Q[m, d]        A = K tile rows from LDS, B = Q from registers
+//   O^T[d, m] = sum_n V^T[d, n] P^T[n, m]    A = V^T from LDS,        B = P from the S^T
+//                                            accumulators (no data movement)
+// Lane l = (m = l % 32, hh = l / 32).  A 32x32 accumulator block holds, in register i of lane
+// l, the element [row 8*(i/4) + 4*hh + i%4][column m].  The B operand of the PV product takes
+// registers 8*kk..8*kk+7 of an S^T block as its 8 contraction slots, so slot (hh, jj) is key
+// 16*kk + 8*(jj/4) + 4*hh + jj%4 of the 32-key block.
+//
+// K and V tiles sit row-major (token rows of 256 bytes) in LDS, written there directly by
+// global_load_lds (no staging registers): a wavefront instruction deposits 4 gathered rows
+// as 1 KB, lane l at byte 16*l, so rows cannot be padded; bank conflicts are avoided by an XOR
+// swizzle instead: the sixteen 16-byte chunks of row r are stored at slot chunk ^ swz(r)
+// (each lane fetches, from global memory, the chunk that belongs at its LDS slot), with
+// swz(r) = 4*(r%4) + 2*((r/4)%2) + (r/8)%2: the 16 rows a 16-byte K read touches land on 16
+// different chunks, and the 4 rows x 64 bytes that half a wavefront touches in a transposing
+// V read land on the four 16-bank groups.
+// The K operand is a plain 16-byte read of a row; the V^T operand is read with the
+// transposing LDS load ds_read_b64_tr_b16: within each group of 16 lanes, lane i receives
+// element (i % 4) of the four 8-byte rows pointed to by lanes i/4, 4 + i/4, 8 + i/4 and
+// 12 + i/4, so pointing lane r of a group at (key slot r/4, dims 4*(r%4)..+3) hands every
+// lane the four keys of its contraction slots at its own head dimension.
+//
+// Online softmax: logits are kept in base-2 units (raw score * softmax_scale * log2 e).
+// m_ref is the reference maximum the accumulated terms are expressed in; it follows the true
+// running maximum lazily: terms are only rescaled when the maximum has grown by more than
+// kLazy (2^8), so that in the common case a tile costs no pass over the accumulator.  Any
+// reference gives the same result; tile masses and the stop test are ratios in one common
+// reference.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace s2o {
+namespace tile {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+typedef __attribute__((address_space(1))) void gvoid;
+typedef __attribute__((address_space(3))) void lvoid;
+
+constexpr int kD = 128;                  // head dim
+constexpr int kBN = 64;                  // key tile
+constexpr int kRowsPerWave = 32;         // query rows of one wavefront
+constexpr int kRowElems = kD;            // K and V rows sit unpadded in LDS (256 B)
+constexpr int kTileElems = kBN * kRowElems;
+constexpr float kLazy = 8.0f;
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 t = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, t);
+}
+
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1); }
+
+// Byte offset, inside its 256-byte global row, of the chunk that lane `lane` of a 4-row load
+// instruction must fetch so that it lands at the right (swizzled) LDS slot; `row0` is the
+// first of the 4 tile rows the instruction covers (lane l covers row row0 + l/16).
+__device__ __forceinline__ int load_chunk_offset(int lane, int row0) {
+  return 16 * ((lane & 15) ^ swz(row0 + (lane >> 4)));
+}
+
+// One 4-row load instruction: 64 lanes x 16 bytes from global memory straight into LDS.
+__device__ __forceinline__ void load_rows_to_lds(const char* lane_src, uint16_t* lds_row0) {
+  __builtin_amdgcn_global_load_lds((const gvoid*)lane_src, (lvoid*)lds_row0, 16, 0, 0);
+}
+
+// Per-lane element offsets of the MFMA operands inside a tile.
+struct Operands {
+  int koff[8];      // K operand: row 32*nb + m, chunk 2*kk + hh, for the 8 contraction steps
+  int voff[4][2];   // V^T operand: [32-dim block][8-key half of a 16-key step]
+  __device__ __forceinline__ void init(int lane) {
+    const int m_ = lane & 31, hh = lane >> 5;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) koff[kk] = m_ * kRowElems + 8 * ((2 * kk + hh) ^ swz(m_));
+    // lane (group g16 = lane/16, r = lane%16) points at key slot r/4 (+ 4 for the upper lane
+    // half), dims 16*(g16&1) + 4*(r%4); the row's swizzle depends on the lane and on which
+    // 8-key half of the 16-key step is read
+    const int rl = ((lane & 15) >> 2) + 4 * (lane >> 5);
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int a8 = 0; a8 < 2; ++a8) {
+        const int chunk = 4 * db + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+        voff[db][a8] = (rl + 8 * a8) * kRowElems + 8 * (chunk ^ swz(rl + 8 * a8)) + 4 * (lane & 1);
+      }
+  }
+};
+
+// Q fragments of a lane's row: dims 16*kk + 8*hh .. +8 for the 8 contraction steps.
+__device__ __forceinline__ void load_q(const uint16_t* qrow, int hh, bf16x8 (&qf)[8]) {
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * hh);
+}
+
+// contraction slots (hh, jj): jj < 4 -> keys key0 + 4*hh + jj, jj >= 4 -> keys key0 + 8 + 4*hh + jj - 4
+__device__ __forceinline__ bf16x8 read_vt(const uint16_t* vt, int key0, const int (&off)[2]) {
+  const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vt + key0 * kRowElems + off[0]));
+  const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vt + key0 * kRowElems + off[1]));
+  const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+  const u32x4 w = {l2.x, l2.y, h2.x, h2.y};
+  return __builtin_bit_cast(bf16x8, w);
+}
+
+// S^T = K Q^T for the key tile at `ks`
+__device__ __forceinline__ void qk_tile(const uint16_t* ks, const Operands& op, const bf16x8 (&qf)[8],
+                                        f32x16 (&s)[2]) {
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[nb][i] = 0.f;
+  // K fragments are fetched from LDS two contraction steps ahead of the MFMA that uses them
+  bf16x8 ka[3][2];
+#pragma unroll
+  for (int pre = 0; pre < 2; ++pre)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+      ka[pre][nb] = *reinterpret_cast<const bf16x8*>(ks + 32 * nb * kRowElems + op.koff[pre]);
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    if (kk + 2 < 8) {
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+        ka[(kk + 2) % 3][nb] = *reinterpret_cast<const bf16x8*>(ks + 32 * nb * kRowElems + op.koff[kk + 2]);
+    }
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+      s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk % 3][nb], qf[kk], s[nb], 0, 0, 0);
+  }
+}
+
+// O^T += V^T P^T with the V tile at `vt`
+__device__ __forceinline__ void pv_tile(const uint16_t* vt, const Operands& op, const bf16x8 (&pb)[4],
+                                        f32x16 (&o)[4]) {
+  // V^T fragments are fetched one contraction step (4 blocks of 32 dims) ahead
+  bf16x8 va[2][4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db) va[0][db] = read_vt(vt, 0, op.voff[db]);
+#pragma unroll
+  for (int st = 0; st < 4; ++st) {
+    if (st + 1 < 4) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db) va[(st + 1) & 1][db] = read_vt(vt, 16 * (st + 1), op.voff[db]);
+    }
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[st & 1][db], pb[st], o[db], 0, 0, 0);
+  }
+}
+
+// What a tile's score step hands to its PV step and to the row statistics.
+struct TileStats {
+  float alpha;   // factor that moves the old terms to the reference used for this tile (1 if unchanged)
+  float mass;    // the tile's softmax mass for this lane's row, in that reference
+  float prev;    // the row's mass so far, in that reference
+  float m_use;   // the reference maximum used for this tile
+  bool grow;     // the reference moved: the accumulator needs alpha
+};
+
+// Softmax numerators of a tile (left in s) and the row statistics.  kMask: apply the causal
+// mask, the tile starting at key position key0 of the segment and the lane's row being qoff.
+template <bool kMask>
+__device__ __forceinline__ TileStats softmax_tile(f32x16 (&s)[2], float c2, float m_ref, float l_run, int key0,
+                                                  int qoff, int hh) {
+  float mx = -INFINITY;
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if (kMask) {
+        const int kpos = key0 + 32 * nb + 8 * (i >> 2) + 4 * hh + (i & 3);
+        if (kpos > qoff) s[nb][i] = -INFINITY;     // CausalMask
+      }
+      mx = fmaxf(mx, s[nb][i]);
+    }
+  mx = fmaxf(mx, __shfl_xor(mx, 32)) * c2;
+  TileStats t;
+  t.grow = mx > m_ref + kLazy;
+  t.m_use = t.grow ? mx : m_ref;
+  float sum = 0.f;
+  const float neg = -t.m_use;
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float pe = __builtin_amdgcn_exp2f(fmaf(s[nb][i], c2, neg));
+      s[nb][i] = pe;
+      sum += pe;
+    }
+  sum += __shfl_xor(sum, 32);
+  t.mass = sum;
+  t.alpha = t.grow ? __builtin_amdgcn_exp2f(m_ref - t.m_use) : 1.0f;
+  t.prev = l_run * t.alpha;
+  return t;
+}
+
+// P^T fragments (bf16) for the four 16-key contraction steps
+__device__ __forceinline__ void pack_p(const f32x16 (&s)[2], bf16x8 (&pb)[4]) {
+#pragma unroll
+  for (int st = 0; st < 4; ++st) {
+    const int nb = st >> 1, k2 = st & 1;
+    u32x4 w;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) w[q] = pack_bf16x2(s[nb][8 * k2 + 2 * q], s[nb][8 * k2 + 2 * q + 1]);
+    pb[st] = __builtin_bit_cast(bf16x8, w);
+  }
+}
+
+// rare: move the accumulator to a new reference maximum (O^T *= alpha)
+__device__ __forceinline__ void rescale(f32x16 (&o)[4], float al, bool gr) {
+  if (__builtin_amdgcn_ballot_w64(gr) != 0ull) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[db][i] *= al;
+  }
+}
+
+__device__ __forceinline__ void zero_acc(f32x16 (&o)[4]) {
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+}
+
+// State buffers: a row's accumulator is kept as 128 fp32 in the accumulator's register order
+// (a lane's 16 values of a 32-dim block contiguous; `sp` = row base + 64*hh).
+__device__ __forceinline__ void store_acc(float* sp, const f32x16 (&o)[4]) {
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      const f32x4 v = {o[db][4 * i4], o[db][4 * i4 + 1], o[db][4 * i4 + 2], o[db][4 * i4 + 3]};
+      *reinterpret_cast<f32x4*>(sp + 16 * db + 4 * i4) = v;
+    }
+}
+__device__ __forceinline__ void load_acc(const float* sp, f32x16 (&o)[4]) {
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(sp + 16 * db + 4 * i4);
+      o[db][4 * i4] = v[0]; o[db][4 * i4 + 1] = v[1]; o[db][4 * i4 + 2] = v[2]; o[db][4 * i4 + 3] = v[3];
+    }
+}
+
+// Normalise and store a lane's share of its output row: dims 32*db + 8*(i/4) + 4*hh + i%4.
+__device__ __forceinline__ void store_o(uint16_t* orow, int hh, const f32x16 (&o)[4], float inv) {
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      u32x2 w;
+      w.x = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
+      w.y = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
+      *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * i4 + 4 * hh) = w;
+    }
+}
+
+// block id -> (head index z*H + h, segment counted from the last, position inside the
+// segment's run of `per_seg` workgroups).  Longest prefixes first.  Consecutive block ids
+// are dealt round-robin to the 8 XCDs, each with its own L2: the workgroups of one
+// (z, h, segment) walk the same keys at about the same time, so they are given ids that land
+// on one XCD (their K/V tiles then hit in that L2), while the XCD of a head rotates with the
+// segment so that heads that stop early and heads that never stop mix evenly on every XCD.
+__device__ __forceinline__ void map_block(int b, int ZH, int per_seg, int& zh, int& nr, int& pos) {
+  if (ZH % 8 == 0) {
+    const int xcd = b & 7, idx = b >> 3, per = ZH / 8;
+    pos = idx % per_seg;
+    const int unit = idx / per_seg;
+    nr = unit / per;
+    zh = ((xcd - nr) & 7) + 8 * (unit % per);
+  } else {
+    pos = b % per_seg;
+    const int unit = b / per_seg;
+    nr = unit / ZH;
+    zh = unit % ZH;
+  }
+}
+
+}  // namespace tile
+}  // namespace s2o

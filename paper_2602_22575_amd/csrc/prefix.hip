@@ -5,9 +5,9 @@
 // One workgroup = 4 wavefronts = 128 permuted query rows of one (batch, head, segment): two
 // query tiles of 64 rows or one of 128, 32 rows per wavefront.  The wavefronts of a segment
 // walk the same KV_perm row, so a gathered 64-token K/V tile is staged in LDS once per
-// workgroup.  MFMA formulation, LDS layouts, the base-2 online softmax with lazy rescaling
-// and the early-stop vote (taken one tile late, the PV product of a tile waiting for it) are
-// those of attention.hip; see there.
+// workgroup.  MFMA formulation, LDS layouts and the base-2 online softmax with lazy rescaling
+// are in attn_tile.h; the early-stop vote is taken one tile late, the PV product of a tile
+// waiting for it.
 //
 // What differs is the tile pipeline.  Because the PV product of tile k runs during step k+1,
 // V tile k is only needed one step after K tile k, so it is also fetched one step later:
@@ -16,33 +16,17 @@
 // 4 wavefronts of under 256 registers two workgroups share a CU: their barriers are
 // independent and one's prologue (Q gather, 2 KB of state per row), stop/drain tail and
 // epilogue overlap the other's tiles.
+#include "attn_tile.h"
 #include "s2o_internal.h"
 
 namespace s2o {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef short i16x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
-typedef __attribute__((address_space(1))) void gvoid;
-typedef __attribute__((address_space(3))) void lvoid;
+using namespace tile;
 
-constexpr int kD = 128, kBN = 64;
-constexpr int kWaves = 4, kThreads = 64 * kWaves, kRowsPerWave = 32;
-constexpr int kRowElems = kD;
-constexpr int kTileElems = kBN * kRowElems;
+constexpr int kWaves = 4, kThreads = 64 * kWaves;
 constexpr size_t kPrefixLds = (size_t)(4 * kTileElems) * 2 + 64;   // K x2, V x2, vote flags
-
-__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  bf16x2 t = {(__bf16)lo, (__bf16)hi};
-  return __builtin_bit_cast(uint32_t, t);
-}
 
 // kNoStop: stop_mode 2 (every prefix tile folded in, the paper's kernel C) as an instantiation
 // of its own, so that neither loop's registers weigh on the other.
@@ -62,32 +46,9 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   const int TJ = a.S / BM;                               // query tiles per segment
   const int JG = (TJ + tpw - 1) / tpw;                   // workgroups per (z,h,n)
 
-  // ---- block -> (z, h, n, jg).  Longest prefixes first.  Consecutive block ids are dealt
-  // round-robin to the 8 XCDs, each with its own L2: the JG workgroups of one (z, h, n) walk
-  // the same KV_perm row at about the same time, so they are given ids that land on one XCD
-  // (their gathered K/V tiles then hit in that L2), while the XCD of a head rotates with the
-  // segment so that heads that stop early and heads that never stop mix evenly on every XCD.
-  int z, h, n, jg;
-  {
-    const int ZH = a.Z * a.H;
-    const int b = blockIdx.x;
-    int zh_, nr;
-    if (ZH % 8 == 0) {
-      const int xcd = b & 7, idx = b >> 3, per = ZH / 8;
-      jg = idx % JG;
-      const int unit = idx / JG;
-      nr = unit / per;
-      zh_ = ((xcd - nr) & 7) + 8 * (unit % per);
-    } else {
-      jg = b % JG;
-      const int unit = b / JG;
-      nr = unit / ZH;
-      zh_ = unit % ZH;
-    }
-    n = a.N - 1 - nr;
-    z = zh_ / a.H;
-    h = zh_ % a.H;
-  }
+  int zh_, nr, jg;
+  map_block(blockIdx.x, a.Z * a.H, JG, zh_, nr, jg);
+  const int n = a.N - 1 - nr, z = zh_ / a.H, h = zh_ % a.H;
   const int g = h / G;
   const uint16_t* Qh = a.Q + z * a.qs[0] + h * a.qs[1];
   const uint16_t* Kh = a.K + z * a.ks[0] + g * a.ks[1];
@@ -107,14 +68,13 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   const bool active = j < TJ;
 
   // ---- loader: every wavefront moves 16 rows of K and 16 rows of V per step, 4 rows per
-  // instruction (lane l: one 16-byte chunk of row 4*group + l/16, straight into LDS).  The
-  // token indices are read two tiles ahead of the K fetch that uses them, so a fetch never
-  // waits for its own index loads; the V fetch of a tile reuses its K fetch's indices.
-  auto swz = [](int r) { return ((r & 3) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1); };
+  // instruction.  The token indices are read two tiles ahead of the K fetch that uses them,
+  // so a fetch never waits for its own index loads; the V fetch of a tile reuses its K
+  // fetch's indices.
   const uint32_t k_stride_bytes = (uint32_t)(a.ks[2] * 2), v_stride_bytes = (uint32_t)(a.vs[2] * 2);
   int goff[4];
 #pragma unroll
-  for (int gi = 0; gi < 4; ++gi) goff[gi] = 16 * ((lane & 15) ^ swz(16 * wave + 4 * gi + (lane >> 4)));
+  for (int gi = 0; gi < 4; ++gi) goff[gi] = load_chunk_offset(lane, 16 * wave + 4 * gi);
   uint32_t tokk[4], tokv[4];            // tokens of the next K tile and of the next V tile
   auto load_index = [&](int t) {        // tokk <- tile t (clamped); only called when ntiles > 0
     const int pt = min(t, ntiles - 1);
@@ -127,18 +87,16 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   auto load_k = [&](int t) {            // K tile t (its tokens are in tokk) -> buffer t & 1
     uint16_t* kd = Ks + (t & 1) * kTileElems;
 #pragma unroll
-    for (int gi = 0; gi < 4; ++gi) {
-      const char* kp = reinterpret_cast<const char*>(Kh) + (uint64_t)tokk[gi] * k_stride_bytes + goff[gi];
-      __builtin_amdgcn_global_load_lds((const gvoid*)kp, (lvoid*)(kd + (16 * wave + 4 * gi) * kRowElems), 16, 0, 0);
-    }
+    for (int gi = 0; gi < 4; ++gi)
+      load_rows_to_lds(reinterpret_cast<const char*>(Kh) + (uint64_t)tokk[gi] * k_stride_bytes + goff[gi],
+                       kd + (16 * wave + 4 * gi) * kRowElems);
   };
   auto load_v = [&](int t) {            // V tile t (its tokens are in tokv) -> buffer t & 1
     uint16_t* vd = Vt + (t & 1) * kTileElems;
 #pragma unroll
-    for (int gi = 0; gi < 4; ++gi) {
-      const char* vp = reinterpret_cast<const char*>(Vh) + (uint64_t)tokv[gi] * v_stride_bytes + goff[gi];
-      __builtin_amdgcn_global_load_lds((const gvoid*)vp, (lvoid*)(vd + (16 * wave + 4 * gi) * kRowElems), 16, 0, 0);
-    }
+    for (int gi = 0; gi < 4; ++gi)
+      load_rows_to_lds(reinterpret_cast<const char*>(Vh) + (uint64_t)tokv[gi] * v_stride_bytes + goff[gi],
+                       vd + (16 * wave + 4 * gi) * kRowElems);
   };
   // the fetches of step t: K(t+1) and V(t); afterwards tokk holds tile t+2, tokv tile t+1
   auto load_step = [&](int t) {
@@ -165,141 +123,27 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
     const int r = min(j, TJ - 1) * BM + kRowsPerWave * part + m_;
     qoff = a.use_q_perm ? a.q_perm[(zh * a.N + n) * a.S + r] : r;
     qoff = min(max(qoff, 0), a.S - 1);
-    const uint16_t* qrow = Qh + (int64_t)(nS + qoff) * a.qs[2];
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk)
-      qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * hh);
+    load_q(Qh + (int64_t)(nS + qoff) * a.qs[2], hh, qf);
   }
-
-  // K operand: row 32*nb + m_, chunk 2*kk + hh -> per-lane byte offsets for the 8 steps
-  int koff[8];
-#pragma unroll
-  for (int kk = 0; kk < 8; ++kk) koff[kk] = m_ * kRowElems + 8 * ((2 * kk + hh) ^ swz(m_));
-  // transposing read of 4 keys x this lane's dimension (see attention.hip)
-  int voff[4][2];
-  {
-    const int rl = ((lane & 15) >> 2) + 4 * (lane >> 5);
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int a8 = 0; a8 < 2; ++a8) {
-        const int chunk = 4 * db + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-        voff[db][a8] = (rl + 8 * a8) * kRowElems + 8 * (chunk ^ swz(rl + 8 * a8)) + 4 * (lane & 1);
-      }
-  }
-  auto read_vt = [&](const uint16_t* vt, int key0, int db) -> bf16x8 {
-    const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vt + key0 * kRowElems + voff[db][0]));
-    const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(vt + key0 * kRowElems + voff[db][1]));
-    u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-    u32x4 w = {l2.x, l2.y, h2.x, h2.y};
-    return __builtin_bit_cast(bf16x8, w);
-  };
+  Operands op;
+  op.init(lane);
 
   // ---- online-softmax state and output accumulator O^T[d-block], resumed from the state
-  // buffers: row (z, h, l) -> acc [128] fp32 in the accumulator's register order, l, m.  The
-  // statistics are needed by the first softmax; the accumulator only by the first PV product,
-  // one step later: its 512 bytes per row are requested after the first tile's scores have
-  // been issued and arrive behind them.
-  constexpr float kLazy = 8.0f;
+  // buffers (row (z, h, l) -> accumulator, l, m).  The statistics are needed by the first
+  // softmax; the accumulator only by the first PV product, one step later: its 512 bytes per
+  // row are requested after the first tile's scores have been issued and arrive behind them.
   const float c2 = a.scale_log2e;
   const int64_t st_row = zh * a.L + nS + qoff;
   float m_ref = a.st_m[st_row], l_run = a.st_l[st_row];
   f32x16 o[4];
-  auto load_acc = [&] {
-    const float* sp = a.st_acc + st_row * kD + 64 * hh;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const f32x4 v = *reinterpret_cast<const f32x4*>(sp + 16 * db + 4 * i4);
-        o[db][4 * i4] = v[0]; o[db][4 * i4 + 1] = v[1]; o[db][4 * i4 + 2] = v[2]; o[db][4 * i4 + 3] = v[3];
-      }
-  };
+  const float* st_acc_row = a.st_acc + st_row * kD + 64 * hh;
   int committed = 0, issued = 0;
 
-  // values a tile's score step hands to its PV step
   f32x16 s[2];
-  float alpha, mass, prev, m_use;
-  bool grow;
-
-  // S^T = K Q^T for key tile buffer kbuf
-  auto qk = [&](int kbuf) {
-    const uint16_t* ks = Ks + kbuf * kTileElems;
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[nb][i] = 0.f;
-    // K fragments are fetched from LDS two contraction steps ahead of the MFMA that uses them
-    bf16x8 ka[3][2];
-#pragma unroll
-    for (int pre = 0; pre < 2; ++pre)
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-        ka[pre][nb] = *reinterpret_cast<const bf16x8*>(ks + 32 * nb * kRowElems + koff[pre]);
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      if (kk + 2 < 8) {
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-          ka[(kk + 2) % 3][nb] = *reinterpret_cast<const bf16x8*>(ks + 32 * nb * kRowElems + koff[kk + 2]);
-      }
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-        s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk % 3][nb], qf[kk], s[nb], 0, 0, 0);
-    }
-  };
-  // softmax numerators (left in s) and the row statistics of the tile
-  auto softmax = [&] {
-    float mx = -INFINITY;
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[nb][i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32)) * c2;
-    grow = mx > m_ref + kLazy;
-    m_use = grow ? mx : m_ref;
-    float sum = 0.f;
-    const float neg = -m_use;
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float pe = __builtin_amdgcn_exp2f(fmaf(s[nb][i], c2, neg));
-        s[nb][i] = pe;
-        sum += pe;
-      }
-    sum += __shfl_xor(sum, 32);
-    mass = sum;
-    alpha = grow ? __builtin_amdgcn_exp2f(m_ref - m_use) : 1.0f;
-    prev = l_run * alpha;
-  };
-  // rare: move the accumulator to a new reference maximum (O^T *= alpha)
-  auto rescale = [&](float al, bool gr) {
-    if (__builtin_amdgcn_ballot_w64(gr) != 0ull) {
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][i] *= al;
-    }
-  };
-  // O^T += V^T P^T with the V tile in buffer vbuf
-  auto pv = [&](int vbuf, const bf16x8 (&pb)[4]) {
-    const uint16_t* vt = Vt + vbuf * kTileElems;
-    // V^T fragments are fetched one contraction step (4 blocks of 32 dims) ahead
-    bf16x8 va[2][4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db) va[0][db] = read_vt(vt, 0, db);
-#pragma unroll
-    for (int st = 0; st < 4; ++st) {
-      if (st + 1 < 4) {
-#pragma unroll
-        for (int db = 0; db < 4; ++db) va[(st + 1) & 1][db] = read_vt(vt, 16 * (st + 1), db);
-      }
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[st & 1][db], pb[st], o[db], 0, 0, 0);
-    }
-  };
+  TileStats ts;
+  auto qk = [&](int kbuf) { qk_tile(Ks + kbuf * kTileElems, op, qf, s); };
+  auto softmax = [&] { ts = softmax_tile<false>(s, c2, m_ref, l_run, 0, 0, hh); };
+  auto pv = [&](int vbuf, const bf16x8 (&pb)[4]) { pv_tile(Vt + vbuf * kTileElems, op, pb, o); };
 
   // ---- prefix tiles in KV_perm order with the early-stop rule: the query tile continues iff
   // some row's tile mass reaches tau * (mass so far).  The wavefronts of a tile vote through
@@ -312,25 +156,14 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   bf16x8 pb_pend[4];
   float alpha_pend = 1.f, l_save = 0.f, m_save = 0.f;
   bool grow_pend = false;
-  auto pack_p = [&] {                   // P^T fragments (bf16) for the four 16-key contraction steps
-#pragma unroll
-    for (int st = 0; st < 4; ++st) {
-      const int nb = st >> 1, k2 = st & 1;
-      u32x4 w;
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        w[q] = pack_bf16x2(s[nb][8 * k2 + 2 * q], s[nb][8 * k2 + 2 * q + 1]);
-      pb_pend[st] = __builtin_bit_cast(bf16x8, w);
-    }
-  };
   auto vote_flags = [&](int step) { return sflag + kWaves * (step & 1); };
   auto publish = [&](int step) {        // after softmax of tile `step`: vote + speculative stats
-    const bool keep = __builtin_amdgcn_ballot_w64(mass >= a.tau * prev) != 0ull;
+    const bool keep = __builtin_amdgcn_ballot_w64(ts.mass >= a.tau * ts.prev) != 0ull;
     if (lane == 0) vote_flags(step)[wave] = keep ? 1 : 0;
     l_save = l_run; m_save = m_ref;
-    l_run = prev + mass; m_ref = m_use;
-    alpha_pend = alpha; grow_pend = grow;
-    pack_p();
+    l_run = ts.prev + ts.mass; m_ref = ts.m_use;
+    alpha_pend = ts.alpha; grow_pend = ts.grow;
+    pack_p(s, pb_pend);
     ++issued;
   };
   auto tile_votes = [&](const int* vf) {
@@ -360,12 +193,12 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
       }
       if (active) {
         qk(it & 1);
-        if (!acc_loaded) { load_acc(); acc_loaded = true; }
+        if (!acc_loaded) { load_acc(st_acc_row, o); acc_loaded = true; }
         softmax();
-        pack_p();
-        rescale(alpha, grow);
+        pack_p(s, pb_pend);
+        rescale(o, ts.alpha, ts.grow);
         pv(it & 1, pb_pend);
-        l_run = prev + mass; m_ref = m_use;
+        l_run = ts.prev + ts.mass; m_ref = ts.m_use;
         ++committed; ++issued;
       }
       __syncthreads();
@@ -378,7 +211,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
       // first tile: scores only
       load_step(0);
       qk(0);
-      load_acc(); acc_loaded = true;
+      load_acc(st_acc_row, o); acc_loaded = true;
       softmax();
       publish(0);
       __syncthreads();
@@ -391,7 +224,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
           if (a.stop_mode == 0) {
             l_run = l_save; m_ref = m_save;
           } else {
-            rescale(alpha_pend, grow_pend);
+            rescale(o, alpha_pend, grow_pend);
             pv((it - 1) & 1, pb_pend);
             ++committed;
           }
@@ -401,7 +234,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
         }
         qk(it & 1);
         load_step(it);
-        rescale(alpha_pend, grow_pend);
+        rescale(o, alpha_pend, grow_pend);
         pv((it - 1) & 1, pb_pend);
         ++committed;
         softmax();
@@ -413,7 +246,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
         if (stop && a.stop_mode == 0) {
           l_run = l_save; m_ref = m_save;
         } else {
-          rescale(alpha_pend, grow_pend);
+          rescale(o, alpha_pend, grow_pend);
           pv((ntiles - 1) & 1, pb_pend);
           ++committed;
         }
@@ -432,19 +265,9 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   }
 
   if (active) {
-    if (!acc_loaded) load_acc();                 // no prefix tile was walked (first segment)
-    // normalise and scatter to the original row: lane holds dims 32*db + 8*(i/4) + 4*hh + i%4
-    const float inv = 1.0f / l_run;
-    uint16_t* orow = Oh + (int64_t)(nS + qoff) * a.os[2];
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        u32x2 w;
-        w.x = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
-        w.y = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
-        *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * i4 + 4 * hh) = w;
-      }
+    if (!acc_loaded) load_acc(st_acc_row, o);    // no prefix tile was walked (first segment)
+    // normalise and scatter to the original row
+    store_o(Oh + (int64_t)(nS + qoff) * a.os[2], hh, o, 1.0f / l_run);
     if (lane == 0 && part == 0) {
       const int64_t ci = zh * (a.L / BM) + (int64_t)n * TJ + j;
       if (a.computed) a.computed[ci] = committed;
