@@ -24,7 +24,7 @@
 //                        list of spans (runs of consecutive buckets that fit the LDS sort).
 //   span_sort_kernel     sorts each span in LDS and writes the token indices at their
 //                        final ranks -> KV_perm.  Linear-time: a second, fine bucketing on
-//                        the score value leaves ~2 keys per sub-bucket, which are ranked by
+//                        the score value leaves a few keys per sub-bucket, which are ranked by
 //                        direct comparison; a span whose keys pile up in one sub-bucket
 //                        (many equal scores) falls back to a bitonic network.
 //   big_sort_kernel      fallback for a bucket that alone exceeds the LDS sort (e.g. all
@@ -46,8 +46,8 @@ constexpr int kD = 128;
 constexpr int kNBMax = 64;         // buckets per prefix row (upper bound)
 constexpr int kBucketAvg = 2048;   // target average bucket population
 constexpr int kSampleStride = 64;  // one sampled score per this many tokens
-constexpr int kSpanCap = 4096;     // elements one span_sort workgroup sorts in LDS
-constexpr int kSubBuckets = 2048;  // fine buckets of the in-LDS sort
+constexpr int kSpanCap = 4032;     // elements one span_sort workgroup sorts in LDS
+constexpr int kSubBuckets = 1024;  // fine buckets of the in-LDS sort
 constexpr int kSubMax = 64;        // a fuller sub-bucket sends the span to the bitonic fallback
 constexpr int kChunkMax = 1024;    // key tokens per score workgroup (halved while the grid is too small)
 constexpr int kCellMax = 1024;     // key tokens per (row, cell) of the bucket counts (16-bit counters)
@@ -622,21 +622,27 @@ __global__ __launch_bounds__(4 * kNBMax) void scan_kernel(PlanArgs a, Scratch sc
   }
 }
 
-constexpr int kSortThreads = 1024;
+constexpr int kSortThreads = 256;
 constexpr int kPerThread = kSubBuckets / kSortThreads;   // sub-bucket counters scanned per thread
 
-__global__ __launch_bounds__(kSortThreads, 8) void span_sort_kernel(PlanArgs a, Scratch sc) {
-  __shared__ uint64_t keys[kSpanCap];
-  __shared__ uint16_t grp[kSpanCap];
-  __shared__ uint32_t start[kSubBuckets + 1];
-  __shared__ uint32_t fill[kSubBuckets];
-  __shared__ uint32_t wsum[kSortThreads / 64];
-  __shared__ uint32_t red[3];          // min / max of the ordered score bits, fullest sub-bucket
+__global__ __launch_bounds__(kSortThreads, 4) void span_sort_kernel(PlanArgs a, Scratch sc) {
+  // One block of LDS, small enough for four workgroups per CU: the span's keys grouped by
+  // sub-bucket, then the sub-bucket offsets and cursors.  The bitonic fallback pads the keys
+  // to a power of two (up to 4096) and may run into the offsets, which it does not use.
+  __shared__ __attribute__((aligned(16))) unsigned char sm[kSpanCap * 8 + (2 * kSubBuckets + 1) * 4 +
+                                                          (kSortThreads / 64 + 3) * 4];
+  static_assert(sizeof(sm) >= 4096 * 8, "the fallback sorts up to 4096 padded keys in place");
+  uint64_t* keys = reinterpret_cast<uint64_t*>(sm);
+  uint32_t* start = reinterpret_cast<uint32_t*>(sm + kSpanCap * 8);    // [kSubBuckets + 1]
+  uint32_t* fill = start + kSubBuckets + 1;                            // [kSubBuckets]
+  uint32_t* wsum = fill + kSubBuckets;                                 // [kSortThreads / 64]
+  uint32_t* red = wsum + kSortThreads / 64;     // min / max of the ordered score bits, fullest sub-bucket
   const int tid = threadIdx.x;
   const uint32_t nspans = min(sc.counters[0], (uint32_t)sc.max_spans);
-  // A workgroup sorts spans blockIdx.x, blockIdx.x + gridDim.x, ...; the pairs of the next span
-  // are requested (into registers) while the current one is sorted.
-  constexpr int kPerLoad = kSpanCap / kSortThreads;
+  // A workgroup sorts spans blockIdx.x, blockIdx.x + gridDim.x, ...  A thread keeps its (up to
+  // kPerLoad) pairs of the span in registers until they are grouped, and requests the next
+  // span's pairs as soon as those registers are free, while the current span is ranked.
+  constexpr int kPerLoad = (kSpanCap + kSortThreads - 1) / kSortThreads;
   int4 sp = make_int4(0, 0, 0, 0);
   uint64_t held[kPerLoad];
   auto fetch = [&](uint32_t w) {
@@ -653,40 +659,42 @@ __global__ __launch_bounds__(kSortThreads, 8) void span_sort_kernel(PlanArgs a, 
   for (uint32_t w = blockIdx.x; w < nspans; w += gridDim.x) {
     const int64_t base = row_base(a, sp.x) + sp.y;
     const int len = sp.z - sp.y;
+    const bool more = w + gridDim.x < nspans;
     if (tid == 0) { red[0] = 0xffffffffu; red[1] = 0u; red[2] = 0u; }
     for (int i = tid; i < kSubBuckets; i += kSortThreads) fill[i] = 0;
-    __syncthreads();
     uint32_t lo = 0xffffffffu, hi = 0u;
 #pragma unroll
     for (int e = 0; e < kPerLoad; ++e) {
-      const int i = tid + e * kSortThreads;
-      if (i < len) {
-        const uint64_t k = held[e];
-        keys[i] = k;
-        const uint32_t o = ~(uint32_t)(k >> 32);   // ordered score bits (ascending = ascending score)
+      if (tid + e * kSortThreads < len) {
+        const uint32_t o = ~(uint32_t)(held[e] >> 32);   // ordered score bits (ascending = ascending score)
         lo = min(lo, o); hi = max(hi, o);
       }
     }
-    if (w + gridDim.x < nspans) fetch(w + gridDim.x);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
       lo = min(lo, (uint32_t)__shfl_xor((int)lo, o));
       hi = max(hi, (uint32_t)__shfl_xor((int)hi, o));
     }
+    __syncthreads();                              // red and fill are initialised
     if ((tid & 63) == 0) { atomicMin(&red[0], lo); atomicMax(&red[1], hi); }
     __syncthreads();
+    const float flo = ordered_to_float(red[0]);
+    const float fhi = ordered_to_float(red[1]);
+    const float range = fhi - flo;
+    const float scale = range > 0.f ? (float)kSubBuckets / range : 0.f;
+    // fine bucket of a key: descending score -> ascending sub-bucket (monotone in the key)
+    auto sub = [&](uint64_t k) {
+      const float f = ordered_to_float(~(uint32_t)(k >> 32));
+      return min(max((int)((fhi - f) * scale), 0), kSubBuckets - 1);
+    };
     bool fallback = len < 64;
     if (!fallback) {
-      const float flo = ordered_to_float(red[0]);
-      const float fhi = ordered_to_float(red[1]);
-      const float range = fhi - flo;
-      const float scale = range > 0.f ? (float)kSubBuckets / range : 0.f;
-      // fine bucket of a key: descending score -> ascending sub-bucket (monotone in the key)
-      auto sub = [&](uint64_t k) {
-        const float f = ordered_to_float(~(uint32_t)(k >> 32));
-        return min(max((int)((fhi - f) * scale), 0), kSubBuckets - 1);
-      };
-      for (int i = tid; i < len; i += kSortThreads) atomicAdd(&fill[sub(keys[i])], 1u);
+      int sb[kPerLoad];
+#pragma unroll
+      for (int e = 0; e < kPerLoad; ++e) {
+        sb[e] = sub(held[e]);
+        if (tid + e * kSortThreads < len) atomicAdd(&fill[sb[e]], 1u);
+      }
       __syncthreads();
       // exclusive scan of the sub-bucket counts: kPerThread per thread, then across threads
       uint32_t cnt[kPerThread], run = 0, mx = 0;
@@ -716,24 +724,30 @@ __global__ __launch_bounds__(kSortThreads, 8) void span_sort_kernel(PlanArgs a, 
       fallback = red[2] > (uint32_t)kSubMax;
       __syncthreads();
       if (!fallback) {
-        for (int i = tid; i < len; i += kSortThreads) {
-          const int sbk = sub(keys[i]);
-          grp[start[sbk] + atomicAdd(&fill[sbk], 1u)] = (uint16_t)i;
-        }
+#pragma unroll
+        for (int e = 0; e < kPerLoad; ++e)
+          if (tid + e * kSortThreads < len) keys[start[sb[e]] + atomicAdd(&fill[sb[e]], 1u)] = held[e];
+        if (more) fetch(w + gridDim.x);
         __syncthreads();
+        // rank inside the sub-bucket by direct comparison
         for (int p = tid; p < len; p += kSortThreads) {
-          const uint64_t k = keys[grp[p]];
+          const uint64_t k = keys[p];
           const int sbk = sub(k);
           const uint32_t s0 = start[sbk], s1 = start[sbk + 1];
           uint32_t rank = s0;
-          for (uint32_t qd = s0; qd < s1; ++qd) rank += keys[grp[qd]] < k ? 1u : 0u;
+          for (uint32_t qd = s0; qd < s1; ++qd) rank += keys[qd] < k ? 1u : 0u;
           a.kv_perm[base + rank] = (int32_t)(uint32_t)k;
         }
       }
     }
     if (fallback) {
       const int n2 = next_pow2(len);
-      for (int i = len + tid; i < n2; i += kSortThreads) keys[i] = ~0ull;
+#pragma unroll
+      for (int e = 0; e < kPerLoad; ++e) {
+        const int i = tid + e * kSortThreads;
+        if (i < n2) keys[i] = i < len ? held[e] : ~0ull;
+      }
+      if (more) fetch(w + gridDim.x);
       __syncthreads();
       bitonic_sort_lds(keys, n2, tid, kSortThreads);
       for (int i = tid; i < len; i += kSortThreads) a.kv_perm[base + i] = (int32_t)(uint32_t)keys[i];
