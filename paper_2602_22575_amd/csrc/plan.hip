@@ -46,8 +46,8 @@ constexpr int kD = 128;
 constexpr int kNBMax = 64;         // buckets per prefix row (upper bound)
 constexpr int kBucketAvg = 2048;   // target average bucket population
 constexpr int kSampleStride = 64;  // one sampled score per this many tokens
-constexpr int kSpanCap = 4032;     // elements one span_sort workgroup sorts in LDS
-constexpr int kSubBuckets = 1024;  // fine buckets of the in-LDS sort
+constexpr int kSpanCap = 4096;     // elements one span_sort workgroup sorts in LDS
+constexpr int kSubBuckets = 2048;  // fine buckets of the in-LDS sort
 constexpr int kSubMax = 64;        // a fuller sub-bucket sends the span to the bitonic fallback
 constexpr int kChunkMax = 1024;    // key tokens per score workgroup (halved while the grid is too small)
 constexpr int kCellMax = 1024;     // key tokens per (row, cell) of the bucket counts (16-bit counters)
@@ -625,18 +625,13 @@ __global__ __launch_bounds__(4 * kNBMax) void scan_kernel(PlanArgs a, Scratch sc
 constexpr int kSortThreads = 256;
 constexpr int kPerThread = kSubBuckets / kSortThreads;   // sub-bucket counters scanned per thread
 
-__global__ __launch_bounds__(kSortThreads, 4) void span_sort_kernel(PlanArgs a, Scratch sc) {
-  // One block of LDS, small enough for four workgroups per CU: the span's keys grouped by
-  // sub-bucket, then the sub-bucket offsets and cursors.  The bitonic fallback pads the keys
-  // to a power of two (up to 4096) and may run into the offsets, which it does not use.
-  __shared__ __attribute__((aligned(16))) unsigned char sm[kSpanCap * 8 + (2 * kSubBuckets + 1) * 4 +
-                                                          (kSortThreads / 64 + 3) * 4];
-  static_assert(sizeof(sm) >= 4096 * 8, "the fallback sorts up to 4096 padded keys in place");
-  uint64_t* keys = reinterpret_cast<uint64_t*>(sm);
-  uint32_t* start = reinterpret_cast<uint32_t*>(sm + kSpanCap * 8);    // [kSubBuckets + 1]
-  uint32_t* fill = start + kSubBuckets + 1;                            // [kSubBuckets]
-  uint32_t* wsum = fill + kSubBuckets;                                 // [kSortThreads / 64]
-  uint32_t* red = wsum + kSortThreads / 64;     // min / max of the ordered score bits, fullest sub-bucket
+__global__ __launch_bounds__(kSortThreads) void span_sort_kernel(PlanArgs a, Scratch sc) {
+  __shared__ uint64_t keys[kSpanCap];           // the span's keys grouped by sub-bucket (fallback: as loaded)
+  static_assert((kSpanCap & (kSpanCap - 1)) == 0, "the fallback pads a span to a power of two in place");
+  __shared__ uint32_t start[kSubBuckets + 1];
+  __shared__ uint32_t fill[kSubBuckets];
+  __shared__ uint32_t wsum[kSortThreads / 64];
+  __shared__ uint32_t red[3];          // min / max of the ordered score bits, fullest sub-bucket
   const int tid = threadIdx.x;
   const uint32_t nspans = min(sc.counters[0], (uint32_t)sc.max_spans);
   // A workgroup sorts spans blockIdx.x, blockIdx.x + gridDim.x, ...  A thread keeps its (up to
