@@ -41,7 +41,7 @@
 extern "C" {
 #endif
 
-#define S2O_VERSION 2
+#define S2O_VERSION 3
 
 enum {
   S2O_OK = 0,
@@ -68,7 +68,12 @@ typedef struct s2o_params {
   float softmax_scale;   /* 0 -> 1/sqrt(D)                                                 */
   int32_t max_prefix_tiles; /* 0: no budget; k > 0: a query tile visits at most the first k
                             tiles of its ranked prefix row (top-k selection, App. A)       */
-  int32_t reserved;      /* must be 0                                                      */
+  int32_t non_causal;    /* 0: causal prefill (the paper's setting).  1: every query attends
+                            every key, as in the non-causal decomposition and top-k
+                            comparisons of App. A: row n of KV_perm / s_K then ranks all L
+                            tokens (rows of L entries, row n at n*L), there is no
+                            own-segment pass and no state buffer, and every query row starts
+                            its walk from the empty softmax state                          */
   int64_t q_stride[3];   /* element strides of Q for (z, h, l); all 0 -> packed [Z,H,L,D]  */
   int64_t k_stride[3];
   int64_t v_stride[3];
@@ -81,10 +86,11 @@ typedef struct s2o_params {
 typedef struct s2o_plan_out {
   int32_t* q_perm;   /* [Z,H,N,S]  segment-local offsets in [0,S), ordered by (s_q desc, offset asc) */
   int32_t* kv_perm;  /* [Z,H,S*N(N-1)/2] packed rows of absolute token indices < n*S,
-                        ordered by (s_k desc, index asc)                                   */
+                        ordered by (s_k desc, index asc); non_causal: [Z,H,N,L], indices < L */
   float* s_q;        /* [Z,H,N,S]  s_Q[n,s] = <Q[nS+s], k_guide>            (Eq. (1)), or NULL */
   float* s_k;        /* packed like kv_perm, indexed by token t (unsorted):
-                        s_K[n,t] = <q_mean[n], K[t]>, t < n*S               (Eq. (2)), or NULL */
+                        s_K[n,t] = <q_mean[n], K[t]>, t < n*S (non_causal: t < L)
+                                                                            (Eq. (2)), or NULL */
   float* q_mean;     /* [Z,H,N,D]  segment means of Q, or NULL                             */
   float* k_guide;    /* [Z,Hkv,D]  mean of the first key segment, or NULL                  */
 } s2o_plan_out;
@@ -108,7 +114,7 @@ int s2o_plan(const void* Q, const void* K, const s2o_params* params, const s2o_p
              void* scratch, size_t scratch_bytes, void* stream);
 
 /* Byte sizes of one counts array ([Z,H,L/B_M] int32) and of the optional attention scratch
- * (the per-row state buffers of the two-pass form, fp32 [Z,H,L,D+2]). */
+ * (the per-row state buffers of the two-pass form, fp32 [Z,H,L,D+2]; 0 when non_causal). */
 int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* scratch_bytes);
 
 /* Step 2 (Alg. 2 + Alg. 3, or Alg. 4 when use_q_perm == 0).
@@ -125,6 +131,8 @@ int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* 
  *            n*(S/B_M)+j; skipped: prefix tiles never loaded.  n*S/B_N - computed - skipped
  *            is 1 when a triggering tile was loaded and discarded (stop_mode 0), else 0.
  *            Tiles beyond max_prefix_tiles count as skipped.  Either may be NULL.
+ *            With non_causal the row of segment n lists L/B_N tiles (for every n, segment 0
+ *            included), tau must be finite, and scratch is ignored.
  *   scratch  NULL: one fused launch (the own-segment window and the prefix walk share
  *            registers).  Otherwise a device buffer, 256-byte aligned, of at least the size
  *            s2o_attention_sizes reports (else S2O_ESCRATCH): the call is then

@@ -40,6 +40,16 @@ Readings of points the paper leaves open (each also listed in the design notes):
     visited).  Segment 0 has no prefix.
   * The "local window W" listed as an input of Alg. 3/4 is never used in their bodies;
     it is read as W = S, i.e. Pass-1 itself.
+  * Non-causal setting (causal=False; the appendix "Why Online Permutation Adds Negligible
+    Overhead" runs its decomposition kernels and its top-k comparison on non-causal
+    attention too, without spelling the algorithm out): every query attends every key.
+    Reading: row n of KV_perm ranks all L tokens by <q_mean[n], K[t]> (rows of L entries,
+    for every n, segment 0 included), there is no Pass-1, and each query row starts the
+    ranked walk from the empty state (m = -inf, l = 0), so its first tile has infinite gain
+    and is always kept.  tau <= 0 (or stop_mode 2 without a budget) reproduces plain softmax
+    attention over all keys.  PARITY UNPINNED against the paper (no worked example); pinned
+    against the plain definition at tau <= 0, the visited-set identity and the masked
+    softmax of a tile budget.
   * Counts, per permuted query tile j of segment n (n*S/B_N prefix tiles exist):
     computed[j] = prefix tiles folded into the state (and so into O); skipped[j] = prefix
     tiles never issued.  A triggering tile that stop_mode 0 discards is in neither, so
@@ -74,8 +84,9 @@ def stable_argsort_desc(s: np.ndarray) -> np.ndarray:
 # ---------------------------------------------------------------------------
 # Dense reference
 # ---------------------------------------------------------------------------
-def dense_attention(Q, K, V, scale=None, rows=None):
-    """O[z,h,i] = sum_{j<=i} softmax_j(scale <Q[z,h,i], K[z,h//G,j]>) V[z,h//G,j].
+def dense_attention(Q, K, V, scale=None, rows=None, causal=True):
+    """O[z,h,i] = sum_{j<=i} softmax_j(scale <Q[z,h,i], K[z,h//G,j]>) V[z,h//G,j]
+    (causal=False: the sum runs over all j).
 
     Q [Z,H,L,D], K,V [Z,Hkv,L,D] float64.  `rows` (optional 1-D index array) restricts
     the computed query rows; the result then has shape [Z,H,len(rows),D]."""
@@ -90,7 +101,8 @@ def dense_attention(Q, K, V, scale=None, rows=None):
             for c0 in range(0, rows.size, 512):
                 r = rows[c0:c0 + 512]
                 x = scale * (Q[z, h, r] @ k.T)                 # [r, L]
-                x[np.arange(L)[None, :] > r[:, None]] = NEG_INF
+                if causal:
+                    x[np.arange(L)[None, :] > r[:, None]] = NEG_INF
                 x -= x.max(axis=1, keepdims=True)
                 p = np.exp(x)
                 O[z, h, c0:c0 + r.size] = (p @ v) / p.sum(axis=1, keepdims=True)
@@ -106,8 +118,18 @@ def kv_row_offset(n: int, S: int) -> int:
     return S * n * (n - 1) // 2
 
 
-def plan(Q, K, S):
-    """Alg. 1.  Returns a dict with
+def kv_row_start(n: int, S: int, L: int, causal: bool = True) -> int:
+    """Start of row n in one head's KV_perm / s_K: packed prefix rows, or rows of L."""
+    return kv_row_offset(n, S) if causal else n * L
+
+
+def kv_row_len(n: int, S: int, L: int, causal: bool = True) -> int:
+    """Keys row n ranks: the n*S tokens before segment n, or all L without causality."""
+    return n * S if causal else L
+
+
+def plan(Q, K, S, causal=True):
+    """Alg. 1 (causal=False: every row ranks all L tokens, see the header).  Returns a dict with
          q_mean [Z,H,N,D], k_guide [Z,Hkv,D], s_q [Z,H,N,S], q_perm int32 [Z,H,N,S]
          (segment-local offsets), s_k [Z,H,P] and kv_perm int32 [Z,H,P] where
          P = S*N(N-1)/2 packs row n (length n*S, absolute token indices) at
@@ -121,7 +143,7 @@ def plan(Q, K, S):
     k_guide = K[:, :, :S, :].mean(axis=2)                          # k_mean[0]
     s_q = np.empty((Z, H, N, S))
     q_perm = np.empty((Z, H, N, S), dtype=np.int32)
-    P = kv_row_offset(N, S)
+    P = kv_row_start(N, S, L, causal)
     s_k = np.empty((Z, H, P))
     kv_perm = np.empty((Z, H, P), dtype=np.int32)
     for z in range(Z):
@@ -130,25 +152,26 @@ def plan(Q, K, S):
             for n in range(N):
                 s_q[z, h, n] = Q[z, h, n * S:(n + 1) * S] @ k_guide[z, g]
                 q_perm[z, h, n] = stable_argsort_desc(s_q[z, h, n])
-                if n == 0:
+                ln = kv_row_len(n, S, L, causal)
+                if ln == 0:
                     continue
-                o = kv_row_offset(n, S)
-                sk = K[z, g, :n * S] @ q_mean[z, h, n]             # causal prefix only
-                s_k[z, h, o:o + n * S] = sk
-                kv_perm[z, h, o:o + n * S] = stable_argsort_desc(sk)
+                o = kv_row_start(n, S, L, causal)
+                sk = K[z, g, :ln] @ q_mean[z, h, n]                # causal: the prefix only
+                s_k[z, h, o:o + ln] = sk
+                kv_perm[z, h, o:o + ln] = stable_argsort_desc(sk)
     return dict(q_mean=q_mean, k_guide=k_guide, s_q=s_q, q_perm=q_perm, s_k=s_k,
                 kv_perm=kv_perm)
 
 
-def identity_maps(Z, H, L, S):
-    """Maps that visit queries and prefix keys in their original order."""
+def identity_maps(Z, H, L, S, causal=True):
+    """Maps that visit queries and keys in their original order."""
     N = L // S
     q_perm = np.broadcast_to(np.arange(S, dtype=np.int32), (Z, H, N, S)).copy()
-    P = kv_row_offset(N, S)
+    P = kv_row_start(N, S, L, causal)
     kv_perm = np.empty((Z, H, P), dtype=np.int32)
-    for n in range(1, N):
-        o = kv_row_offset(n, S)
-        kv_perm[:, :, o:o + n * S] = np.arange(n * S, dtype=np.int32)
+    for n in range(N):
+        o, ln = kv_row_start(n, S, L, causal), kv_row_len(n, S, L, causal)
+        kv_perm[:, :, o:o + ln] = np.arange(ln, dtype=np.int32)
     return q_perm, kv_perm
 
 
@@ -191,7 +214,8 @@ def pass1(q, k, v, scale, BM, BN):
 
 
 def attention(Q, K, V, q_perm, kv_perm, S, BM, BN, tau, stop_mode=0, scale=None,
-              forced_computed=None, heads=None, segments=None, return_gain=False, max_tiles=None):
+              forced_computed=None, heads=None, segments=None, return_gain=False, max_tiles=None,
+              causal=True):
     """Alg. 2 + Alg. 3.  Returns (O [Z,H,L,D] float64, computed int32 [Z,H,L/BM],
     skipped int32 [Z,H,L/BM]); counts are indexed by permuted tile: entry n*(S/BM)+j is
     the j-th tile of Q~_n.
@@ -207,7 +231,9 @@ def attention(Q, K, V, q_perm, kv_perm, S, BM, BN, tau, stop_mode=0, scale=None,
       issued, budgeted-out ones included.
     heads / segments: optional subsets (others are left zero) for sampled checks.
     return_gain: also return a dict {(z,h,n): array [S/BM, n*S/BN]} of max-row gains for
-      the tiles that were evaluated (nan elsewhere)."""
+      the tiles that were evaluated (nan elsewhere).
+    causal=False: no Pass-1; row n of kv_perm lists all L tokens and every query row starts
+      from the empty state (see the header)."""
     Z, H, L, D = Q.shape
     G = H // K.shape[1]
     N = L // S
@@ -223,12 +249,16 @@ def attention(Q, K, V, q_perm, kv_perm, S, BM, BN, tau, stop_mode=0, scale=None,
             k_all, v_all = K[z, g], V[z, g]
             for n in (range(N) if segments is None else segments):
                 seg = slice(n * S, (n + 1) * S)
-                m1, l1, a1 = pass1(Q[z, h, seg], k_all[seg], v_all[seg], scale, BM, BN)
                 qp = q_perm[z, h, n].astype(np.int64)
                 qt = Q[z, h, seg][qp]                               # Gather(Q_n, Q_perm[n])
-                m, l, acc = m1[qp].copy(), l1[qp].copy(), a1[qp].copy()
-                nK = n * S // BN
-                row = kv_perm[z, h, kv_row_offset(n, S):kv_row_offset(n, S) + n * S].astype(np.int64)
+                if causal:
+                    m1, l1, a1 = pass1(Q[z, h, seg], k_all[seg], v_all[seg], scale, BM, BN)
+                    m, l, acc = m1[qp].copy(), l1[qp].copy(), a1[qp].copy()
+                else:
+                    m, l, acc = np.full(S, NEG_INF), np.zeros(S), np.zeros((S, D))
+                o_row, ln = kv_row_start(n, S, L, causal), kv_row_len(n, S, L, causal)
+                nK = ln // BN
+                row = kv_perm[z, h, o_row:o_row + ln].astype(np.int64)
                 gn = np.full((TJ, nK), np.nan)
                 for j in range(TJ):
                     r = slice(j * BM, (j + 1) * BM)
@@ -240,7 +270,8 @@ def attention(Q, K, V, q_perm, kv_perm, S, BM, BN, tau, stop_mode=0, scale=None,
                         T = row[kt * BN:(kt + 1) * BN]
                         x = scale * (qt[r] @ k_all[T].T)
                         cand, mass, prev = online_softmax_update(st, x, v_all[T])
-                        gain = float((mass / prev).max())
+                        with np.errstate(divide="ignore"):           # prev = 0: an empty state, gain = inf
+                            gain = float((mass / prev).max())
                         gn[j, kt] = gain
                         issued += 1
                         stop = forced is None and stop_mode != 2 and gain < tau
@@ -261,12 +292,12 @@ def attention(Q, K, V, q_perm, kv_perm, S, BM, BN, tau, stop_mode=0, scale=None,
 
 
 def gain_profile(Q, K, V, q_perm, kv_perm, S, BM, BN, stop_mode=0, scale=None,
-                 heads=None, segments=None):
+                 heads=None, segments=None, causal=True):
     """Max-row gain of every (query tile, prefix tile) with stopping disabled.  In both
     stop modes the state before a stop does not depend on tau, so for any tau the stop
     position of tile j is the first k with gain[j,k] < tau."""
     out = attention(Q, K, V, q_perm, kv_perm, S, BM, BN, tau=0.0, stop_mode=stop_mode,
-                    scale=scale, heads=heads, segments=segments, return_gain=True)
+                    scale=scale, heads=heads, segments=segments, return_gain=True, causal=causal)
     return out[3]
 
 
@@ -280,11 +311,12 @@ def counts_from_gain(gain_row: np.ndarray, tau: float, stop_mode: int = 0):
     return (k if stop_mode == 0 else k + 1), nK - (k + 1)
 
 
-def attention_visited_set(Q, K, V, q_perm, kv_perm, S, BM, BN, tau, stop_mode=0, scale=None):
+def attention_visited_set(Q, K, V, q_perm, kv_perm, S, BM, BN, tau, stop_mode=0, scale=None, causal=True):
     """Independent formulation: at step k the gain of row i is
          sum_{t in T_k} e^{x_it} / sum_{t in J0(i) u T_0..T_{k-1}} e^{x_it},
     J0(i) = own-segment keys up to i, and the output is exact softmax attention over the
-    visited set.  No running maximum, no rescaling: one global shift per row."""
+    visited set.  No running maximum, no rescaling: one global shift per row.
+    causal=False: J0 is empty, the rows list all L keys and the first tile is always kept."""
     Z, H, L, D = Q.shape
     G = H // K.shape[1]
     N = L // S
@@ -298,25 +330,31 @@ def attention_visited_set(Q, K, V, q_perm, kv_perm, S, BM, BN, tau, stop_mode=0,
             g = h // G
             k, v = K[z, g], V[z, g]
             for n in range(N):
-                nK = n * S // BN
-                kv_row = kv_perm[z, h, kv_row_offset(n, S):kv_row_offset(n, S) + n * S].astype(np.int64)
+                o_row, ln = kv_row_start(n, S, L, causal), kv_row_len(n, S, L, causal)
+                nK = ln // BN
+                kv_row = kv_perm[z, h, o_row:o_row + ln].astype(np.int64)
+                span = (n + 1) * S if causal else L                           # keys a row may see
                 for j in range(TJ):
                     rows = n * S + q_perm[z, h, n, j * BM:(j + 1) * BM].astype(np.int64)
-                    x = scale * (Q[z, h, rows] @ k[:(n + 1) * S].T)          # [BM, (n+1)S]
-                    x[np.arange((n + 1) * S)[None, :] > rows[:, None]] = NEG_INF
+                    x = scale * (Q[z, h, rows] @ k[:span].T)                  # [BM, span]
+                    if causal:
+                        x[np.arange(span)[None, :] > rows[:, None]] = NEG_INF
                     e = np.exp(x - x.max(axis=1, keepdims=True))
-                    denom = e[:, n * S:].sum(axis=1)                          # J0 mass
+                    denom = e[:, n * S:].sum(axis=1) if causal else np.zeros(BM)   # J0 mass
                     issued = nK
                     ncommit = nK
                     for kt in range(nK):
                         T = kv_row[kt * BN:(kt + 1) * BN]
                         mass = e[:, T].sum(axis=1)
-                        if (mass / denom).max() < tau:
+                        with np.errstate(divide="ignore"):
+                            gain = (mass / denom).max()
+                        if gain < tau:
                             issued = kt + 1
                             ncommit = kt if stop_mode == 0 else kt + 1
                             break
                         denom = denom + mass
-                    vis = np.concatenate([kv_row[:ncommit * BN], np.arange(n * S, (n + 1) * S)])
+                    own = np.arange(n * S, (n + 1) * S) if causal else np.arange(0)
+                    vis = np.concatenate([kv_row[:ncommit * BN], own])
                     O[z, h, rows] = (e[:, vis] @ v[vis]) / e[:, vis].sum(axis=1, keepdims=True)
                     computed[z, h, n * TJ + j] = ncommit
                     skipped[z, h, n * TJ + j] = nK - issued

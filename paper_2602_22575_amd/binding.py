@@ -24,7 +24,7 @@ class S2OParams(C.Structure):
                 ("kv_heads", C.c_int32), ("seq_len", C.c_int32), ("head_dim", C.c_int32),
                 ("seg_len", C.c_int32), ("block_m", C.c_int32), ("block_n", C.c_int32),
                 ("use_q_perm", C.c_int32), ("stop_mode", C.c_int32), ("softmax_scale", C.c_float),
-                ("max_prefix_tiles", C.c_int32), ("reserved", C.c_int32),
+                ("max_prefix_tiles", C.c_int32), ("non_causal", C.c_int32),
                 ("q_stride", C.c_int64 * 3), ("k_stride", C.c_int64 * 3),
                 ("v_stride", C.c_int64 * 3), ("o_stride", C.c_int64 * 3)]
 
@@ -89,13 +89,13 @@ def _check(rc: int):
 
 def make_params(Z, H, Hkv, L, D, S, BM=64, BN=64, use_q_perm=1, stop_mode=0, softmax_scale=0.0,
                 q_stride=(0, 0, 0), k_stride=(0, 0, 0), v_stride=(0, 0, 0),
-                o_stride=(0, 0, 0), max_prefix_tiles=0) -> S2OParams:
+                o_stride=(0, 0, 0), max_prefix_tiles=0, non_causal=0) -> S2OParams:
     p = S2OParams()
     p.struct_size = C.sizeof(S2OParams)
     p.batch, p.q_heads, p.kv_heads, p.seq_len, p.head_dim = Z, H, Hkv, L, D
     p.seg_len, p.block_m, p.block_n = S, BM, BN
     p.use_q_perm, p.stop_mode, p.softmax_scale = use_q_perm, stop_mode, softmax_scale
-    p.max_prefix_tiles, p.reserved = max_prefix_tiles, 0
+    p.max_prefix_tiles, p.non_causal = max_prefix_tiles, non_causal
     for name, val in (("q_stride", q_stride), ("k_stride", k_stride), ("v_stride", v_stride),
                       ("o_stride", o_stride)):
         setattr(p, name, (C.c_int64 * 3)(*val))
@@ -141,7 +141,8 @@ def s2o_plan(Q, K, params: S2OParams, want_scores: bool = True, scratch=None, st
              maps=None) -> Plan:
     """Step 1.  Q, K: torch CUDA bf16 tensors [Z,H,L,D] / [Z,Hkv,L,D].  Returns device
     tensors; the call is asynchronous on the current (or given) torch stream.
-    maps: optional (q_perm [Z,H,N,S], kv_perm [Z,H,max(P,4)]) int32 tensors to write into."""
+    maps: optional (q_perm [Z,H,N,S], kv_perm [Z,H,max(P,4)]) int32 tensors to write into
+    (P = entries of the key rows of one head: S*N(N-1)/2, or N*L when params.non_causal)."""
     import torch
     lib = load_library()
     sz = s2o_plan_sizes(params)
@@ -149,7 +150,7 @@ def s2o_plan(Q, K, params: S2OParams, want_scores: bool = True, scratch=None, st
     Z, H, Hkv, L, D, S = (params.batch, params.q_heads, params.kv_heads, params.seq_len,
                           params.head_dim, params.seg_len)
     N = L // S
-    P = S * N * (N - 1) // 2
+    P = N * L if params.non_causal else S * N * (N - 1) // 2
     if maps is not None:
         out = Plan(q_perm=maps[0], kv_perm=maps[1])
         if (out.q_perm.numel() != Z * H * N * S or out.kv_perm.numel() != Z * H * max(P, 4)
@@ -197,7 +198,7 @@ def s2o_attention(Q, K, V, params: S2OParams, q_perm, kv_perm, tau: float, O=Non
         computed = torch.empty((Z, H, L // params.block_m), dtype=torch.int32, device=dev)
     if skipped is None:
         skipped = torch.empty((Z, H, L // params.block_m), dtype=torch.int32, device=dev)
-    if two_pass and scratch is None:
+    if two_pass and scratch is None and sz["scratch"] > 0:
         scratch = torch.empty(sz["scratch"], dtype=torch.uint8, device=dev)
     if not two_pass:
         scratch = None
@@ -221,7 +222,8 @@ def s2o_attention_local(Q, K, V, params: S2OParams, scratch=None, stream=None):
 
 def s2o_attention_prefix(Q, K, V, params: S2OParams, q_perm, kv_perm, tau: float, scratch, O=None,
                          computed=None, skipped=None, stream=None):
-    """Pass 2 (Alg. 3) alone, resuming from the state s2o_attention_local left in `scratch`."""
+    """Pass 2 (Alg. 3) alone, resuming from the state s2o_attention_local left in `scratch`
+    (None when params.non_causal: there is no state)."""
     import torch
     lib = load_library()
     dev = Q.device
@@ -234,6 +236,6 @@ def s2o_attention_prefix(Q, K, V, params: S2OParams, q_perm, kv_perm, tau: float
         skipped = torch.empty((Z, H, L // params.block_m), dtype=torch.int32, device=dev)
     _check(lib.s2o_attention_prefix(Q.data_ptr(), K.data_ptr(), V.data_ptr(), C.byref(params),
                                     _ptr(q_perm), _ptr(kv_perm), float(tau), O.data_ptr(),
-                                    computed.data_ptr(), skipped.data_ptr(), scratch.data_ptr(),
-                                    scratch.numel(), _stream_handle(stream)))
+                                    computed.data_ptr(), skipped.data_ptr(), _ptr(scratch),
+                                    0 if scratch is None else scratch.numel(), _stream_handle(stream)))
     return O, computed, skipped

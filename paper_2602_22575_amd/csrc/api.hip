@@ -16,7 +16,7 @@ int hip_fail(hipError_t e) {
 }
 
 struct Shape {
-  int Z, H, Hkv, L, D, S, N;
+  int Z, H, Hkv, L, D, S, N, nc;
   int64_t qs[3], ks[3], vs[3], os[3];
 };
 
@@ -44,7 +44,8 @@ int check_params(const s2o_params* p, Shape* s, bool for_plan = false) {
   if (p->seq_len % p->seg_len != 0) return S2O_EINVAL;
   if (p->use_q_perm != 0 && p->use_q_perm != 1) return S2O_EINVAL;
   if (p->stop_mode < 0 || p->stop_mode > 2) return S2O_EINVAL;
-  if (p->max_prefix_tiles < 0 || p->reserved != 0) return S2O_EINVAL;
+  if (p->max_prefix_tiles < 0) return S2O_EINVAL;
+  if (p->non_causal != 0 && p->non_causal != 1) return S2O_EINVAL;
   if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) return S2O_EINVAL;
   if (p->head_dim != 128) return S2O_EUNSUPPORTED;
   if ((p->block_m != 64 && p->block_m != 128) || p->block_n != 64) return S2O_EUNSUPPORTED;
@@ -52,7 +53,7 @@ int check_params(const s2o_params* p, Shape* s, bool for_plan = false) {
   if (for_plan && p->seg_len > 8192) return S2O_EUNSUPPORTED;   // a segment's query scores are sorted in LDS
   if ((int64_t)p->batch * p->q_heads * (p->seq_len / p->seg_len) > (1 << 24)) return S2O_EUNSUPPORTED;
   s->Z = p->batch; s->H = p->q_heads; s->Hkv = p->kv_heads; s->L = p->seq_len;
-  s->D = p->head_dim; s->S = p->seg_len; s->N = p->seq_len / p->seg_len;
+  s->D = p->head_dim; s->S = p->seg_len; s->N = p->seq_len / p->seg_len; s->nc = p->non_causal;
   if (!fill_strides(p->q_stride, s->qs, s->H, s->L, s->D)) return S2O_EINVAL;
   if (!fill_strides(p->k_stride, s->ks, s->Hkv, s->L, s->D)) return S2O_EINVAL;
   if (!fill_strides(p->v_stride, s->vs, s->Hkv, s->L, s->D)) return S2O_EINVAL;
@@ -72,7 +73,7 @@ const char* s2o_strerror(int code) {
   switch (code) {
     case S2O_OK: return "ok";
     case S2O_EINVAL: return "invalid argument";
-    case S2O_EUNSUPPORTED: return "unsupported configuration (need D=128, B_M in {64,128}, B_N=64, S%B_M==0; s2o_plan: S<=8192)";
+    case S2O_EUNSUPPORTED: return "unsupported configuration (need D=128, B_M in {64,128}, B_N=64, S%B_M==0; s2o_plan: S<=8192; no own-segment pass when non_causal)";
     case S2O_ESCRATCH: return "scratch buffer missing, misaligned or too small";
     case S2O_EHIP: return "HIP runtime error (see s2o_last_hip_error)";
     default: return "unknown error code";
@@ -88,14 +89,14 @@ int s2o_plan_sizes(const s2o_params* params, size_t* q_perm_bytes, size_t* kv_pe
   const int rc = check_params(params, &s, true);
   if (rc != S2O_OK) return rc;
   const size_t zh = (size_t)s.Z * s.H;
-  const size_t P = (size_t)s2o::kv_row_offset(s.N, s.S);
+  const size_t P = (size_t)s2o::kv_rows_total(s.N, s.S, s.L, s.nc);
   if (q_perm_bytes) *q_perm_bytes = zh * s.L * 4;
   if (kv_perm_bytes) *kv_perm_bytes = zh * P * 4;
   if (s_q_bytes) *s_q_bytes = zh * s.L * 4;
   if (s_k_bytes) *s_k_bytes = zh * P * 4;
   if (q_mean_bytes) *q_mean_bytes = zh * s.N * s.D * 4;
   if (k_guide_bytes) *k_guide_bytes = (size_t)s.Z * s.Hkv * s.D * 4;
-  if (scratch_bytes) *scratch_bytes = s2o::plan_scratch_bytes(s.Z, s.H, s.Hkv, s.L, s.S);
+  if (scratch_bytes) *scratch_bytes = s2o::plan_scratch_bytes(s.Z, s.H, s.Hkv, s.L, s.S, s.nc);
   return S2O_OK;
 }
 
@@ -105,11 +106,11 @@ int s2o_plan(const void* Q, const void* K, const s2o_params* params, const s2o_p
   const int rc = check_params(params, &s, true);
   if (rc != S2O_OK) return rc;
   if (!Q || !K || !out || !out->q_perm) return S2O_EINVAL;
-  if (s.N > 1 && !out->kv_perm) return S2O_EINVAL;
+  if ((s.N > 1 || s.nc) && !out->kv_perm) return S2O_EINVAL;
   if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(out->q_perm, 16) ||
       misaligned(out->kv_perm, 16) || misaligned(out->s_k, 16))
     return S2O_EINVAL;
-  const size_t need = s2o::plan_scratch_bytes(s.Z, s.H, s.Hkv, s.L, s.S);
+  const size_t need = s2o::plan_scratch_bytes(s.Z, s.H, s.Hkv, s.L, s.S, s.nc);
   if (!scratch || misaligned(scratch, 256) || scratch_bytes < need) return S2O_ESCRATCH;
 
   s2o::PlanArgs a;
@@ -118,6 +119,7 @@ int s2o_plan(const void* Q, const void* K, const s2o_params* params, const s2o_p
   a.q_perm = out->q_perm; a.kv_perm = out->kv_perm;
   a.s_q = out->s_q; a.s_k = out->s_k; a.q_mean = out->q_mean; a.k_guide = out->k_guide;
   a.Z = s.Z; a.H = s.H; a.Hkv = s.Hkv; a.L = s.L; a.S = s.S; a.N = s.N;
+  a.non_causal = s.nc;
   for (int i = 0; i < 3; ++i) { a.qs[i] = s.qs[i]; a.ks[i] = s.ks[i]; }
   a.scratch = scratch; a.scratch_bytes = scratch_bytes;
   const hipError_t e = s2o::launch_plan(a, (hipStream_t)stream);
@@ -129,7 +131,7 @@ int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* 
   const int rc = check_params(params, &s);
   if (rc != S2O_OK) return rc;
   if (counts_bytes) *counts_bytes = (size_t)s.Z * s.H * (s.L / params->block_m) * 4;
-  if (scratch_bytes) *scratch_bytes = s2o::attention_state_bytes(s.Z, s.H, s.L);
+  if (scratch_bytes) *scratch_bytes = s.nc ? 0 : s2o::attention_state_bytes(s.Z, s.H, s.L);
   return S2O_OK;
 }
 
@@ -143,16 +145,21 @@ int attention_call(int passes, const void* Q, const void* K, const void* V, cons
   Shape s;
   const int rc = check_params(params, &s);
   if (rc != S2O_OK) return rc;
+  if (s.nc) {                               // no own-segment pass and no state: the walk is everything
+    if (passes == 1) return S2O_EUNSUPPORTED;
+    passes = 2;
+  }
   const bool walk = passes != 1;            // the prefix walk is part of this call
   if (!Q || !K || !V) return S2O_EINVAL;
   if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(V, 16)) return S2O_EINVAL;
   if (walk) {
     if (!O || misaligned(O, 16)) return S2O_EINVAL;
     if (params->use_q_perm && !q_perm) return S2O_EINVAL;
-    if (s.N > 1 && (!kv_perm || misaligned(kv_perm, 16))) return S2O_EINVAL;
+    if ((s.N > 1 || s.nc) && (!kv_perm || misaligned(kv_perm, 16))) return S2O_EINVAL;
     if (tau != tau) return S2O_EINVAL;
+    if (s.nc && isinf(tau)) return S2O_EINVAL;   // the first tile's test would be inf * 0
   }
-  if (passes != 0 &&
+  if (passes != 0 && !s.nc &&
       (!scratch || misaligned(scratch, 256) || scratch_bytes < s2o::attention_state_bytes(s.Z, s.H, s.L)))
     return S2O_ESCRATCH;
 
@@ -164,7 +171,7 @@ int attention_call(int passes, const void* Q, const void* K, const void* V, cons
   a.q_perm = q_perm; a.kv_perm = kv_perm; a.computed = computed; a.skipped = skipped;
   a.Z = s.Z; a.H = s.H; a.Hkv = s.Hkv; a.L = s.L; a.S = s.S; a.N = s.N;
   a.BM = params->block_m;
-  if (passes != 0) {
+  if (passes != 0 && !s.nc) {
     const size_t rows = (size_t)s.Z * s.H * s.L;
     a.st_acc = (float*)scratch;
     a.st_l = a.st_acc + rows * s.D;
@@ -172,6 +179,7 @@ int attention_call(int passes, const void* Q, const void* K, const void* V, cons
   }
   a.use_q_perm = params->use_q_perm; a.stop_mode = params->stop_mode;
   a.max_tiles = params->max_prefix_tiles;
+  a.non_causal = s.nc;
   a.tau = tau;
   const float scale = params->softmax_scale > 0.f ? params->softmax_scale : 1.0f / sqrtf((float)s.D);
   a.scale_log2e = scale * 1.4426950408889634f;

@@ -55,8 +55,8 @@ constexpr int kSub = 64;           // key tokens per LDS tile of the score kerne
 constexpr int kKStride = 136;      // bf16 elements per K row in LDS (272 B)
 constexpr int kBigGrid = 64;       // workgroups of the fallback sort
 
-__host__ __device__ inline int row_buckets(int n, int S) {
-  int64_t nb = (int64_t)n * S / kBucketAvg;
+__host__ __device__ inline int row_buckets(int64_t len) {
+  const int64_t nb = len / kBucketAvg;
   return nb < 1 ? 1 : (nb > kNBMax ? kNBMax : (int)nb);
 }
 
@@ -100,10 +100,10 @@ struct Scratch {
 
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S) {
+static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S, int non_causal) {
   const int64_t N = L / S;
   const int64_t rows = (int64_t)Z * H * N;
-  const int64_t P = kv_row_offset(N, S);
+  const int64_t P = kv_rows_total(N, S, L, non_causal);
   Scratch s;
   s.max_spans = (int64_t)Z * H * (3 * P / kSpanCap + 2 * N) + 8;
   // one workgroup per (KV head, 128 rows, chunk): keep at least ~1024 of them in the grid
@@ -115,7 +115,7 @@ static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S) {
   // bucket counts are kept per (row, cell of tokens); one workgroup of the counting and scatter
   // passes handles one cell: as large as the staging area allows unless the grid gets too small
   s.cell = kCellMax;
-  while (s.cell > 256 && rows * ((L / 2 + s.cell - 1) / s.cell) < 2048) s.cell /= 2;
+  while (s.cell > 256 && rows * (((non_causal ? L : L / 2) + s.cell - 1) / s.cell) < 2048) s.cell /= 2;
   s.maxch = (L + s.cell - 1) / s.cell;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return (char*)base + o; };
@@ -136,8 +136,8 @@ static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S) {
   return s;
 }
 
-size_t plan_scratch_bytes(int Z, int H, int Hkv, int L, int S) {
-  return carve(nullptr, Z, H, Hkv, L, S).total;
+size_t plan_scratch_bytes(int Z, int H, int Hkv, int L, int S, int non_causal) {
+  return carve(nullptr, Z, H, Hkv, L, S, non_causal).total;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
   const int m_ = lane & 31, hh = lane >> 5;
   const int rb = 4 * rbg + wave;
 
-  auto row_limit = [&](int r) { return r < R ? (r % a.N) * a.S : 0; };
+  auto row_limit = [&](int r) { return r < R ? (int)kv_row_len(r % a.N, a.S, a.L, a.non_causal) : 0; };
   // token limits: of the workgroup's rows (uniform) and of this wavefront's rows
   int lim_wg = 0, lim_wave = 0;
   for (int i = 0; i < 128; ++i) lim_wg = max(lim_wg, row_limit(128 * rbg + i));
@@ -330,7 +330,8 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
   const int rr = min(r, R - 1);
   const int64_t zh = (int64_t)z * a.H + g * G + rr / a.N;
   const int64_t row_id = zh * a.N + rr % a.N;
-  const int64_t base = zh * kv_row_offset(a.N, a.S) + kv_row_offset(rr % a.N, a.S);
+  const int64_t base = zh * kv_rows_total(a.N, a.S, a.L, a.non_causal) +
+                       kv_row_start(rr % a.N, a.S, a.L, a.non_causal);
   float* skdst = (a.s_k ? a.s_k : sc.sk) + base;
 
   // B fragments: 3 split terms x 8 contraction steps
@@ -413,7 +414,7 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
 __device__ inline int64_t row_base(const PlanArgs& a, int64_t row_id) {
   const int n = (int)(row_id % a.N);
   const int64_t zh = row_id / a.N;
-  return zh * kv_row_offset(a.N, a.S) + kv_row_offset(n, a.S);
+  return zh * kv_rows_total(a.N, a.S, a.L, a.non_causal) + kv_row_start(n, a.S, a.L, a.non_causal);
 }
 
 // Bucket of a score = number of the row's (descending) splitters above it.  Two levels, both
@@ -442,7 +443,7 @@ __global__ __launch_bounds__(256) void count_kernel(PlanArgs a, Scratch sc) {
   __shared__ uint32_t cnt[kNBMax];
   const int64_t row_id = blockIdx.x / sc.maxch;
   const int cellno = blockIdx.x % sc.maxch;
-  const int lim = (int)(row_id % a.N) * a.S;    // prefix length of this row
+  const int lim = (int)kv_row_len(row_id % a.N, a.S, a.L, a.non_causal);   // keys this row ranks
   const int t_begin = cellno * sc.cell;
   if (t_begin >= lim) return;
   const int t_end = min(t_begin + sc.cell, lim);
@@ -482,7 +483,7 @@ __global__ __launch_bounds__(256) void scatter_kernel(PlanArgs a, Scratch sc) {
   __shared__ uint32_t sdst[kCellMax];
   const int64_t row_id = blockIdx.x / sc.maxch;
   const int cellno = blockIdx.x % sc.maxch;
-  const int lim = (int)(row_id % a.N) * a.S;
+  const int lim = (int)kv_row_len(row_id % a.N, a.S, a.L, a.non_causal);
   const int t_begin = cellno * sc.cell;
   if (t_begin >= lim) return;
   const int t_end = min(t_begin + sc.cell, lim);
@@ -541,12 +542,13 @@ __global__ __launch_bounds__(256) void splitter_kernel(PlanArgs a, Scratch sc) {
   const int64_t row_id = blockIdx.x;
   const int n = (int)(row_id % a.N);
   float* out = sc.splitters + row_id * kNBMax;
-  const int nb = n > 0 ? row_buckets(n, a.S) : 1;
+  const int len = (int)kv_row_len(n, a.S, a.L, a.non_causal);
+  const int nb = row_buckets(len);
   if (nb == 1) {
     if (threadIdx.x < kNBMax) out[threadIdx.x] = -INFINITY;
     return;
   }
-  const int ns = n * a.S / kSampleStride;
+  const int ns = len / kSampleStride;
   const int n2 = next_pow2(ns);
   const float* smp = sc.samples + row_id * (a.L / kSampleStride);
   for (int i = threadIdx.x; i < n2; i += 256) keys[i] = i < ns ? sort_key(smp[i], (uint32_t)i) : ~0ull;
@@ -567,11 +569,11 @@ __global__ __launch_bounds__(4 * kNBMax) void scan_kernel(PlanArgs a, Scratch sc
   __shared__ uint32_t tot[kNBMax];
   __shared__ uint32_t bstart[kNBMax + 1];
   const int64_t row_id = blockIdx.x;
-  const int n = (int)(row_id % a.N);
-  if (n == 0) return;
+  const int len = (int)kv_row_len(row_id % a.N, a.S, a.L, a.non_causal);
+  if (len == 0) return;
   const int b = threadIdx.x % kNBMax, q = threadIdx.x / kNBMax;
-  const int nb = row_buckets(n, a.S);
-  const int nch = (n * a.S + sc.cell - 1) / sc.cell;
+  const int nb = row_buckets(len);
+  const int nch = (len + sc.cell - 1) / sc.cell;
   const int c0 = (nch * q) / 4, c1 = (nch * (q + 1)) / 4;   // this thread's chunk range
   const uint16_t* ch = sc.chist + row_id * sc.maxch * kNBMax;
   uint32_t* co = sc.coffs + row_id * sc.maxch * kNBMax;
@@ -600,7 +602,7 @@ __global__ __launch_bounds__(4 * kNBMax) void scan_kernel(PlanArgs a, Scratch sc
       off += cnt;
     }
     if (off > span_begin) lspan[ns++] = make_int2((int)span_begin, (int)off);
-    if (off != (uint32_t)(n * a.S)) sc.counters[2] = 2u;
+    if (off != (uint32_t)len) sc.counters[2] = 2u;
     nsp[0] = ns; nsp[1] = nbig;
     // one reservation per list instead of one (slow, serialised) atomic per span
     gbase[0] = ns ? atomicAdd(&sc.counters[0], ns) : 0u;
@@ -806,7 +808,7 @@ __global__ __launch_bounds__(256) void big_sort_kernel(PlanArgs a, Scratch sc) {
 
 // ---------------------------------------------------------------------------------------
 hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
-  const Scratch sc = carve(a.scratch, a.Z, a.H, a.Hkv, a.L, a.S);
+  const Scratch sc = carve(a.scratch, a.Z, a.H, a.Hkv, a.L, a.S, a.non_causal);
   if (sc.total > a.scratch_bytes) return hipErrorInvalidValue;
   if ((int64_t)a.Z * a.H * a.N * sc.maxch > 0x7fffffff) return hipErrorInvalidValue;
   const int64_t rows = (int64_t)a.Z * a.H * a.N;
@@ -835,7 +837,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
     const size_t lds = (size_t)n2 * 8 + 4 * kD * 4;
     hipLaunchKernelGGL(pool_sq_sort_kernel, dim3((unsigned)rows), dim3(256), lds, stream, a, sc);
   }
-  if (a.N > 1) {
+  if (a.N > 1 || a.non_causal) {
     const int RB = (G * a.N + 31) / 32;
     const int RBG = (RB + 3) / 4;
     const int nchunks = (a.L + sc.chunk - 1) / sc.chunk;

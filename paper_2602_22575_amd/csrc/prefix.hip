@@ -55,9 +55,11 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   const uint16_t* Vh = a.V + z * a.vs[0] + g * a.vs[1];
   uint16_t* Oh = a.O + z * a.os[0] + h * a.os[1];
   const int64_t zh = (int64_t)z * a.H + h;
-  const int32_t* kvrow = a.kv_perm + zh * kv_row_offset(a.N, a.S) + kv_row_offset(n, a.S);
+  const int32_t* kvrow = a.kv_perm + zh * kv_rows_total(a.N, a.S, a.L, a.non_causal) +
+                         kv_row_start(n, a.S, a.L, a.non_causal);
   const int nS = n * a.S;
-  const int nK_all = nS / kBN;                 // prefix tiles that exist for this segment
+  // key tiles this segment's row of KV_perm lists: its prefix, or everything without causality
+  const int nK_all = (int)(kv_row_len(n, a.S, a.L, a.non_causal) / kBN);
   // prefix tiles this launch may walk: at most the budget
   const int ntiles = a.max_tiles > 0 ? min(nK_all, a.max_tiles) : nK_all;
 
@@ -133,10 +135,16 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   // softmax; the accumulator only by the first PV product, one step later: its 512 bytes per
   // row are requested after the first tile's scores have been issued and arrive behind them.
   const float c2 = a.scale_log2e;
+  // Without causality there is no own-segment pass: every row starts from the empty state.
   const int64_t st_row = zh * a.L + nS + qoff;
-  float m_ref = a.st_m[st_row], l_run = a.st_l[st_row];
+  float m_ref = -INFINITY, l_run = 0.f;
+  if (!a.non_causal) { m_ref = a.st_m[st_row]; l_run = a.st_l[st_row]; }
   f32x16 o[4];
   const float* st_acc_row = a.st_acc + st_row * kD + 64 * hh;
+  auto init_acc = [&] {
+    if (a.non_causal) zero_acc(o);
+    else load_acc(st_acc_row, o);
+  };
   int committed = 0, issued = 0;
 
   f32x16 s[2];
@@ -193,7 +201,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
       }
       if (active) {
         qk(it & 1);
-        if (!acc_loaded) { load_acc(st_acc_row, o); acc_loaded = true; }
+        if (!acc_loaded) { init_acc(); acc_loaded = true; }
         softmax();
         pack_p(s, pb_pend);
         rescale(o, ts.alpha, ts.grow);
@@ -211,7 +219,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
       // first tile: scores only
       load_step(0);
       qk(0);
-      load_acc(st_acc_row, o); acc_loaded = true;
+      init_acc(); acc_loaded = true;
       softmax();
       publish(0);
       __syncthreads();
@@ -265,7 +273,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   }
 
   if (active) {
-    if (!acc_loaded) load_acc(st_acc_row, o);    // no prefix tile was walked (first segment)
+    if (!acc_loaded) init_acc();                 // no prefix tile was walked (first segment)
     // normalise and scatter to the original row
     store_o(Oh + (int64_t)(nS + qoff) * a.os[2], hh, o, 1.0f / l_run);
     if (lane == 0 && part == 0) {

@@ -10,6 +10,18 @@ namespace s2o {
 // Packed start of prefix row n (n >= 1) inside one head's KV_perm / s_K array.
 __host__ __device__ inline int64_t kv_row_offset(int64_t n, int64_t S) { return S * n * (n - 1) / 2; }
 
+// Rows of KV_perm / s_K for one head.  Causal (the paper's setting): row n ranks the n*S
+// tokens before segment n and the rows are packed.  Without causality (params.non_causal,
+// the setting of the paper's non-causal decomposition and top-k comparisons) every row
+// ranks all L tokens.
+__host__ __device__ inline int64_t kv_row_len(int64_t n, int64_t S, int64_t L, int nc) { return nc ? L : n * S; }
+__host__ __device__ inline int64_t kv_row_start(int64_t n, int64_t S, int64_t L, int nc) {
+  return nc ? n * L : kv_row_offset(n, S);
+}
+__host__ __device__ inline int64_t kv_rows_total(int64_t N, int64_t S, int64_t L, int nc) {
+  return nc ? N * L : kv_row_offset(N, S);
+}
+
 // Runs `setup` (kernel attributes such as the dynamic LDS limit are per device) once per
 // device, before the first launch there; other host threads wait until it is done.  A failed
 // setup is retried by the next call.
@@ -42,6 +54,7 @@ struct AttnArgs {
   int Z, H, Hkv, L, S, N;
   int BM;  // query tile rows (64 or 128); the key tile is 64 tokens
   int use_q_perm, stop_mode;
+  int non_causal; // every query attends every key: no own-segment pass, rows of L ranked keys
   int max_tiles;  // > 0: a query tile visits at most this many prefix tiles
   float tau;
   float scale_log2e;  // softmax_scale * log2(e): logits are kept in base-2 units
@@ -58,12 +71,13 @@ struct PlanArgs {
   float* q_mean;
   float* k_guide;
   int Z, H, Hkv, L, S, N;
+  int non_causal;
   int64_t qs[3], ks[3];
   void* scratch;
   size_t scratch_bytes;
 };
 
-size_t plan_scratch_bytes(int Z, int H, int Hkv, int L, int S);
+size_t plan_scratch_bytes(int Z, int H, int Hkv, int L, int S, int non_causal);
 size_t attention_state_bytes(int Z, int H, int L);
 hipError_t launch_plan(const PlanArgs& a, hipStream_t stream);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t stream);

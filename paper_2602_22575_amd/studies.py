@@ -8,6 +8,8 @@
         B  + indexed gather with identity maps          (stop_mode 2)
         C  + ranked maps from s2o_plan                  (stop_mode 2)
         D  + the early-stop vote, never stopping        (stop_mode 0, tau = -1)
+      followed by B, C, D in the non-causal setting (params.non_causal: every query walks all
+      L keys; there is no contiguous non-causal kernel, so no A).
   python -m paper_2602_22575_amd.studies plan-table   ranking time over (L, S) (the paper's
       retrieval-latency table in "Additional details on end-to-end operator performance"),
       with time * S / L^2 to check the L^2 / S law.
@@ -84,6 +86,36 @@ def abcd():
         print(f"| {w.L} | {w.S} | {a:.2f} ({flops / a / 1e9:.0f}) | {b:.2f} | {c:.2f} | {d:.2f} | "
               f"{b / a:.3f} | {c / b:.3f} | {d / c:.3f} |", flush=True)
         del Qd, Kd, Vd, O, state, plan, qi, ki
+        torch.cuda.empty_cache()
+    print()
+    print("| L | S | non-causal: B identity gather ms (TFLOP/s) | C ranked gather ms | D + stop vote ms | C/B | D/C |")
+    print("|---|---|---|---|---|---|---|")
+    for name in ("llama8k", "llama32k", "llama128k"):
+        w = inputs.workload(name)
+        Qd, Kd, Vd = (_dev(x) for x in inputs.make_qkv(w))
+        T = w.L // 64
+        flops = 4.0 * 64 * 64 * w.D * T * T * w.Z * w.H
+        O = torch.empty_like(Qd)
+        cnt = torch.empty((w.Z, w.H, w.L // w.BM), dtype=torch.int32, device="cuda:0")
+        cnt2 = torch.empty_like(cnt)
+        kw = dict(O=O, computed=cnt, skipped=cnt2)
+        p2 = s2o.make_params(w.Z, w.H, w.Hkv, w.L, w.D, w.S, w.BM, w.BN, stop_mode=2, non_causal=1)
+        p0 = s2o.make_params(w.Z, w.H, w.Hkv, w.L, w.D, w.S, w.BM, w.BN, stop_mode=0, non_causal=1)
+        plan = s2o.s2o_plan(Qd, Kd, p2, want_scores=False)
+        N = w.L // w.S
+        qi = torch.arange(w.S, dtype=torch.int32, device="cuda:0").expand(w.Z, w.H, N, w.S).contiguous()
+        ki = torch.arange(w.L, dtype=torch.int32, device="cuda:0").repeat(N).expand(w.Z, w.H, N * w.L).contiguous()
+        variants = [lambda: s2o.s2o_attention(Qd, Kd, Vd, p2, qi, ki, -1.0, **kw),
+                    lambda: s2o.s2o_attention(Qd, Kd, Vd, p2, plan.q_perm, plan.kv_perm, -1.0, **kw),
+                    lambda: s2o.s2o_attention(Qd, Kd, Vd, p0, plan.q_perm, plan.kv_perm, -1.0, **kw)]
+        times = [[] for _ in variants]
+        for rep in range(3):
+            for i, fn in enumerate(variants):
+                times[i].append(_timed(fn, 1))
+        b_, c, d = (float(np.median(t)) for t in times)
+        print(f"| {w.L} | {w.S} | {b_:.2f} ({flops / b_ / 1e9:.0f}) | {c:.2f} | {d:.2f} | {c / b_:.3f} | {d / c:.3f} |",
+              flush=True)
+        del Qd, Kd, Vd, O, plan, qi, ki
         torch.cuda.empty_cache()
 
 

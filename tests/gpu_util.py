@@ -19,15 +19,17 @@ def bits_of(t: torch.Tensor) -> np.ndarray:
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def gpu_plan(w, Qd, Kd):
-    p = params_for(w)
+def gpu_plan(w, Qd, Kd, non_causal=0):
+    p = params_for(w, non_causal=non_causal)
     out = s2o.s2o_plan(Qd, Kd, p, want_scores=True)
     torch.cuda.synchronize()
     return out, {k: getattr(out, k).cpu().numpy() for k in ("q_perm", "kv_perm", "s_q", "s_k", "q_mean", "k_guide")}
 
 
-def gpu_attention(w, Qd, Kd, Vd, q_perm, kv_perm, tau, stop_mode=0, use_q_perm=1, two_pass=True, max_tiles=0):
-    p = params_for(w, stop_mode=stop_mode, use_q_perm=use_q_perm, max_prefix_tiles=max_tiles)
+def gpu_attention(w, Qd, Kd, Vd, q_perm, kv_perm, tau, stop_mode=0, use_q_perm=1, two_pass=True, max_tiles=0,
+                  non_causal=0):
+    p = params_for(w, stop_mode=stop_mode, use_q_perm=use_q_perm, max_prefix_tiles=max_tiles,
+                   non_causal=non_causal)
     O, c, s = s2o.s2o_attention(Qd, Kd, Vd, p, q_perm, kv_perm, tau, two_pass=two_pass)
     torch.cuda.synchronize()
     return bits_of(O), c.cpu().numpy(), s.cpu().numpy()

@@ -65,18 +65,19 @@ def check_perm_against_oracle(perm_gpu, perm_orc, s_orc, tol):
     return int(diff.size), nruns
 
 
-def check_plan(w, Qb, Kb, plan_gpu, heads=None, exact=False, segments=None):
+def check_plan(w, Qb, Kb, plan_gpu, heads=None, exact=False, segments=None, causal=True):
     """plan_gpu: dict of numpy arrays (q_perm, kv_perm, s_q, s_k, q_mean, k_guide) from
     the HIP path.  The oracle is run head by head (one query head + its KV head at a time).
+    causal=False: the non-causal setting (every row ranks all L tokens).
     Returns a stats dict."""
-    S, N = w.S, w.N
+    S, N, L = w.S, w.N, w.L
     stats = dict(q_mismatch=0, q_runs=0, kv_mismatch=0, kv_runs=0, rows=0, max_sk_err_over_bound=0.0)
     for z in range(w.Z):
         for h in (range(w.H) if heads is None else heads):
             g = h // w.G
             Q = to_f64(Qb[z:z + 1, h:h + 1])
             K = to_f64(Kb[z:z + 1, g:g + 1])
-            ref = orc.plan(Q, K, S)
+            ref = orc.plan(Q, K, S, causal=causal)
             np.testing.assert_allclose(plan_gpu["k_guide"][z, g], ref["k_guide"][0, 0], rtol=0,
                                        atol=2e-6 * np.abs(K).max())
             np.testing.assert_allclose(plan_gpu["q_mean"][z, h], ref["q_mean"][0, 0], rtol=0,
@@ -93,19 +94,20 @@ def check_plan(w, Qb, Kb, plan_gpu, heads=None, exact=False, segments=None):
                 mm, runs = check_perm_against_oracle(qp, ref["q_perm"][0, 0, n], sq_o, score_tol(bound))
                 stats["q_mismatch"] += mm
                 stats["q_runs"] += runs
-                if n == 0:
+                ln = orc.kv_row_len(n, S, L, causal)
+                if ln == 0:
                     continue
-                o = orc.kv_row_offset(n, S)
-                sk_g = plan_gpu["s_k"][z, h, o:o + n * S]
-                sk_o = ref["s_k"][0, 0, o:o + n * S]
-                bound = np.abs(K[0, 0, :n * S]) @ np.abs(ref["q_mean"][0, 0, n])
+                o = orc.kv_row_start(n, S, L, causal)
+                sk_g = plan_gpu["s_k"][z, h, o:o + ln]
+                sk_o = ref["s_k"][0, 0, o:o + ln]
+                bound = np.abs(K[0, 0, :ln]) @ np.abs(ref["q_mean"][0, 0, n])
                 err = np.abs(sk_g - sk_o)
                 stats["max_sk_err_over_bound"] = max(stats["max_sk_err_over_bound"], float((err / bound).max()))
                 assert np.all(err <= score_tol(bound)), f"s_K error {err.max()} (h={h}, n={n})"
-                kp = plan_gpu["kv_perm"][z, h, o:o + n * S]
+                kp = plan_gpu["kv_perm"][z, h, o:o + ln]
                 assert np.array_equal(kp, np.argsort(-sk_g, kind="stable")), \
                     f"KV_perm is not the stable argsort of s_K (h={h}, n={n})"
-                mm, runs = check_perm_against_oracle(kp, ref["kv_perm"][0, 0, o:o + n * S], sk_o,
+                mm, runs = check_perm_against_oracle(kp, ref["kv_perm"][0, 0, o:o + ln], sk_o,
                                                      score_tol(bound))
                 stats["kv_mismatch"] += mm
                 stats["kv_runs"] += runs
@@ -141,13 +143,14 @@ def check_counts(gain_row, tau, stop_mode, computed, skipped):
 
 
 def check_attention(w, Qb, Kb, Vb, q_perm, kv_perm, tau, stop_mode, O_gpu_bits, computed, skipped,
-                    heads=None, segments=None, gains=None, use_q_perm=True, max_tiles=0):
+                    heads=None, segments=None, gains=None, use_q_perm=True, max_tiles=0, causal=True):
     """Compares one s2o_attention result with the oracle run on the same maps, one query head
     (with its KV head) at a time.  Returns stats (robust/ambiguous tile counts, max-abs and
     relative MSE of O) and the gain profiles (reusable for another tau).
     max_tiles > 0: the run had a tile budget -- the stop rule is checked on the first
     max_tiles gains of each row and the tiles beyond the budget must be reported skipped.
-    stop_mode 2: no stop rule -- every tile inside the budget must be folded in."""
+    stop_mode 2: no stop rule -- every tile inside the budget must be folded in.
+    causal=False: the non-causal setting (rows of L keys, no own-segment pass)."""
     S, N, BM, BN = w.S, w.N, w.BM, w.BN
     TJ = S // BM
     hs = list(range(w.H)) if heads is None else list(heads)
@@ -162,15 +165,16 @@ def check_attention(w, Qb, Kb, Vb, q_perm, kv_perm, tau, stop_mode, O_gpu_bits, 
             qp = q_perm[z:z + 1, h:h + 1] if use_q_perm else orc.identity_maps(1, 1, w.L, S)[0]
             kp = kv_perm[z:z + 1, h:h + 1]
             if (z, h) not in gains and stop_mode != 2:
-                gains[(z, h)] = orc.gain_profile(Q, K, V, qp, kp, S, BM, BN, stop_mode=stop_mode, segments=ns)
+                gains[(z, h)] = orc.gain_profile(Q, K, V, qp, kp, S, BM, BN, stop_mode=stop_mode, segments=ns,
+                                                 causal=causal)
             gz = gains.get((z, h))
             for n in ns:
                 for j in range(TJ):
                     c = int(computed[z, h, n * TJ + j]); s = int(skipped[z, h, n * TJ + j])
-                    if n == 0:
+                    nK = orc.kv_row_len(n, S, w.L, causal) // BN
+                    if nK == 0:
                         assert (c, s) == (0, 0)
                         continue
-                    nK = n * S // BN
                     budget = min(nK, max_tiles) if max_tiles > 0 else nK
                     if stop_mode == 2:
                         assert (c, s) == (budget, nK - budget)
@@ -180,7 +184,7 @@ def check_attention(w, Qb, Kb, Vb, q_perm, kv_perm, tau, stop_mode, O_gpu_bits, 
                     else:
                         ambiguous += 1
             O_ref, _, _ = orc.attention(Q, K, V, qp, kp, S, BM, BN, tau=0.0, stop_mode=stop_mode,
-                                        forced_computed=computed[z:z + 1, h:h + 1], segments=ns)
+                                        forced_computed=computed[z:z + 1, h:h + 1], segments=ns, causal=causal)
             O_gpu = to_f64(O_gpu_bits[z, h])
             for n in ns:
                 a = O_gpu[n * S:(n + 1) * S]

@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert declared == set(b.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.s2o_version() == 2
+    assert lib.s2o_version() == 3
 
 
 def test_struct_layout_matches_header(lib):
@@ -43,6 +43,12 @@ def test_size_queries():
     asz = b.s2o_attention_sizes(p)
     assert asz["counts"] == 32 * (131072 // 64) * 4
     assert asz["scratch"] == 32 * 131072 * (128 + 2) * 4      # fp32 acc, l, m per query row
+    # non-causal setting: rows of L ranked keys for every segment, no state buffer
+    pn = b.make_params(1, 32, 8, 131072, 128, 2048, non_causal=1)
+    szn = b.s2o_plan_sizes(pn)
+    assert szn["kv_perm"] == 32 * N * 131072 * 4 and szn["s_k"] == szn["kv_perm"]
+    assert szn["q_perm"] == sz["q_perm"] and szn["scratch"] >= 32 * N * 131072 * 8
+    assert b.s2o_attention_sizes(pn)["scratch"] == 0
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -57,6 +63,7 @@ def test_size_queries():
     (dict(S=16384, L=32768), b.S2O_EUNSUPPORTED),
     (dict(stop_mode=3), b.S2O_EINVAL),
     (dict(max_prefix_tiles=-1), b.S2O_EINVAL),
+    (dict(non_causal=2), b.S2O_EINVAL),
     (dict(use_q_perm=5), b.S2O_EINVAL),
     (dict(softmax_scale=-1.0), b.S2O_EINVAL),
     (dict(q_stride=(0, 0, 100)), b.S2O_EINVAL),   # row stride not 16-byte aligned / < D
@@ -108,6 +115,15 @@ def test_null_and_scratch_errors_come_before_any_hip_call(lib):
     assert lib.s2o_attention(*bad) == b.S2O_ESCRATCH
     bad = list(args); bad[10] = C.c_void_p(0x10010); bad[11] = 1 << 40
     assert lib.s2o_attention(*bad) == b.S2O_ESCRATCH
+    # non-causal setting: no own-segment pass, the threshold must be finite, kv_perm needed even for N = 1
+    pn = b.make_params(1, 4, 2, 1024, 128, 256, non_causal=1)
+    assert lib.s2o_attention_local(fake, fake, fake, C.byref(pn), fake, 1 << 40, None) == b.S2O_EUNSUPPORTED
+    nargs = list(args); nargs[3] = C.byref(pn)
+    bad = list(nargs); bad[6] = C.c_float(float("inf"))
+    assert lib.s2o_attention(*bad) == b.S2O_EINVAL
+    p1 = b.make_params(1, 4, 2, 256, 128, 256, non_causal=1)
+    bad = list(args); bad[3] = C.byref(p1); bad[5] = None
+    assert lib.s2o_attention(*bad) == b.S2O_EINVAL
     p.struct_size = 8
     assert lib.s2o_attention(*args) == b.S2O_EINVAL
     assert lib.s2o_strerror(b.S2O_ESCRATCH).decode().startswith("scratch")

@@ -458,3 +458,72 @@ def test_mixed128k_sampled(gpu):
     structured, for both query tile shapes (64x64 and 128x64)."""
     _sampled_case("mixed128k", plan_heads=[2, 29], attn_samples=[(2, [3]), (29, [40])], taus=(5e-3,))
     _sampled_case("mixed128k", plan_heads=[], attn_samples=[(2, [3]), (29, [40])], taus=(5e-3,), BM=128)
+
+
+# ---------------------------------------------------------------- non-causal setting
+def test_tiny_noncausal_plan_and_attention(tiny):
+    """params.non_causal: rows of L ranked keys for every segment, no own-segment pass, every
+    query row starts from the empty state.  Plan parity, tau <= 0 against plain softmax
+    attention over all keys, positive thresholds in both stop modes, and the tile budget."""
+    w, (Qb, Kb, Vb), (Qd, Kd, Vd) = tiny
+    _say("case: tiny non-causal plan")
+    plan, pg = gu.gpu_plan(w, Qd, Kd, non_causal=1)
+    assert pg["kv_perm"].shape == (w.Z, w.H, w.N * w.L)
+    stats = parity.check_plan(w, Qb, Kb, pg, causal=False)
+    _say("   plan stats", stats)
+    assert stats["rows"] == w.H * w.N
+    Q, K, V = (parity.to_f64(x) for x in (Qb, Kb, Vb))
+    dense = orc.dense_attention(Q, K, V, causal=False)
+    nK = w.L // w.BN
+    for stop_mode in (0, 1):
+        gains = {(0, 0): orc.gain_profile(Q, K, V, pg["q_perm"], pg["kv_perm"], w.S, w.BM, w.BN,
+                                          stop_mode=stop_mode, causal=False)}
+        for tau in (0.0, -1.0, 0.01, 0.05):
+            if tau > 0:
+                tau = parity.pick_tau(gains, tau)
+            _say(f"case: tiny non-causal attention tau={tau} stop_mode={stop_mode}")
+            Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, stop_mode, non_causal=1)
+            st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, stop_mode, Ob, c, s,
+                                        gains=gains, causal=False)
+            gains = st.pop("gains")
+            _say("  ", st, "issued share", 1 - s.sum() / (nK * s.size))
+            assert np.all(c >= 1)                    # the first tile is always kept
+            if tau <= 0:
+                assert np.all(s == 0) and np.all(c == nK)
+                err = np.abs(parity.to_f64(Ob) - dense)
+                assert err.max() <= parity.O_MAX_ABS
+                assert (err ** 2).sum() / (dense ** 2).sum() <= parity.O_REL_MSE
+            else:
+                assert st["ambiguous"] == 0 and (s > 0).any()
+    for k in (1, 5, 1000):
+        _say(f"case: tiny non-causal budget k={k} stop_mode=2")
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, 0.3, 2, max_tiles=k, non_causal=1)
+        parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], 0.3, 2, Ob, c, s, max_tiles=k, causal=False)
+        assert np.all(c == min(k, nK)) and np.all(s == nK - min(k, nK))
+    # identity maps and original query order, no stop rule: plain attention again
+    import torch
+    qi, ki = orc.identity_maps(w.Z, w.H, w.L, w.S, causal=False)
+    Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, torch.from_numpy(qi).cuda(), torch.from_numpy(ki).cuda(), -1.0, 2,
+                                use_q_perm=0, non_causal=1)
+    assert np.abs(parity.to_f64(Ob) - dense).max() <= parity.O_MAX_ABS
+
+
+def test_llama8k_noncausal_sampled(gpu):
+    """Non-causal setting at 8K (GQA, 32 query heads): plan parity on two heads, attention
+    parity on sampled (head, segment) pairs with the GPU's own maps."""
+    w = inputs.workload("llama8k")
+    Qb, Kb, Vb = inputs.make_qkv(w)
+    Qd, Kd, Vd = (gu.to_dev(x) for x in (Qb, Kb, Vb))
+    _say("case: llama8k non-causal plan")
+    plan, pg = gu.gpu_plan(w, Qd, Kd, non_causal=1)
+    stats = parity.check_plan(w, Qb, Kb, pg, heads=[3, 28], causal=False)
+    _say("   plan stats", stats)
+    for tau, stop_mode in ((2e-3, 0), (0.0, 0), (5e-3, 1)):
+        _say(f"case: llama8k non-causal attention tau={tau} stop_mode={stop_mode}")
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, stop_mode, non_causal=1)
+        for h, segs in ((3, [0, w.N - 1]), (28, [w.N // 2])):
+            st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, stop_mode, Ob, c, s,
+                                        heads=[h], segments=segs, causal=False)
+            st.pop("gains")
+            _say(f"   head {h} segments {segs}:", st)
+            assert st["ambiguous"] <= 0.02 * (st["robust"] + st["ambiguous"]) + 1

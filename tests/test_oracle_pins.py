@@ -384,3 +384,137 @@ def test_bf16_conversions_roundtrip():
         [1.0, -2.0, 0.10009765625]
     # ties round to even mantissa
     assert orc.f64_to_bf16_bits(np.array([1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8])).tolist() == [0x3F80, 0x3F82]
+
+
+# ---------------------------------------------------------------- non-causal setting
+def py_s2o_noncausal(q, k, v, S, BM, BN, tau, stop_mode, max_tiles, scale):
+    """Literal model of the non-causal reading, one head, pure Python lists: every segment
+    ranks all L keys by <segment mean of q, k> (score desc, index asc); a permuted query
+    tile walks that list in tiles of BN keys from nothing, the first tile is always kept,
+    a later tile triggers when every row's (tile weight / weight so far) < tau."""
+    L, D = len(q), len(q[0])
+    N = L // S
+    dot = lambda a, b: sum(x * y for x, y in zip(a, b))
+    W = [[math.exp(scale * dot(q[i], k[j])) for j in range(L)] for i in range(L)]
+    kguide = [sum(k[s][d] for s in range(S)) / S for d in range(D)]
+    out = [None] * L
+    counts, rows_of_maps = [], []
+    for n in range(N):
+        qmean = [sum(q[n * S + s][d] for s in range(S)) / S for d in range(D)]
+        sq = [dot(q[n * S + s], kguide) for s in range(S)]
+        qperm = sorted(range(S), key=lambda s: (-sq[s], s))
+        sk = [dot(qmean, k[t]) for t in range(L)]
+        kvperm = sorted(range(L), key=lambda t: (-sk[t], t))
+        rows_of_maps.append((qperm, kvperm))
+        for j in range(S // BM):
+            rows = [n * S + qperm[j * BM + i] for i in range(BM)]
+            visited = []
+            nK = L // BN
+            budget = nK if max_tiles is None else min(nK, max_tiles)
+            issued = folded = 0
+            for kt in range(budget):
+                T = kvperm[kt * BN:(kt + 1) * BN]
+                issued += 1
+                trig = False
+                if visited and stop_mode != 2:
+                    trig = all(sum(W[i][t] for t in T) / sum(W[i][t] for t in visited) < tau for i in rows)
+                if trig and stop_mode == 0:
+                    break
+                visited = visited + T
+                folded += 1
+                if trig:
+                    break
+            for i in rows:
+                tot = sum(W[i][t] for t in visited)
+                out[i] = [sum(W[i][t] * v[t][d] for t in visited) / tot for d in range(D)]
+            counts.append((folded, nK - issued))
+    return out, counts, rows_of_maps
+
+
+def test_noncausal_dense_matches_torch_sdpa_and_tau_zero_walk():
+    """causal=False: the dense reference equals a library attention routine, and the ranked
+    walk with tau <= 0 (any maps) equals it."""
+    import torch
+    Q, K, V = rand_qkv(1, 4, 2, 32, 8)
+    ref = orc.dense_attention(Q, K, V, causal=False)
+    G = 2
+    tq, tk, tv = (torch.from_numpy(x) for x in (Q, np.repeat(K, G, axis=1), np.repeat(V, G, axis=1)))
+    lib = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=False).numpy()
+    np.testing.assert_allclose(ref, lib, rtol=0, atol=1e-12)
+    causal_lib = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True).numpy()
+    np.testing.assert_allclose(orc.dense_attention(Q, K, V), causal_lib, rtol=0, atol=1e-12)
+    assert np.abs(ref - causal_lib).max() > 1e-3          # the flag does something
+    S, BM, BN = 8, 4, 4
+    p = orc.plan(Q, K, S, causal=False)
+    assert p["kv_perm"].shape == (1, 4, (32 // S) * 32)
+    for tau in (0.0, -1.0):
+        O, c, s = orc.attention(Q, K, V, p["q_perm"], p["kv_perm"], S, BM, BN, tau, causal=False)
+        np.testing.assert_allclose(O, ref, rtol=0, atol=1e-12)
+        assert (c == 32 // BN).all() and (s == 0).all()
+    rng = np.random.default_rng(5)
+    kv = p["kv_perm"].copy().reshape(1, 4, 32 // S, 32)
+    for h in range(4):
+        for n in range(32 // S):
+            kv[0, h, n] = rng.permutation(32)
+    O2, _, _ = orc.attention(Q, K, V, p["q_perm"], kv.reshape(1, 4, -1), S, BM, BN, 0.0, causal=False)
+    np.testing.assert_allclose(O2, ref, rtol=0, atol=1e-12)
+
+
+def test_noncausal_plan_rows_rank_all_tokens():
+    Q, K, _ = rand_qkv(1, 2, 1, 48, 4)
+    S, L = 16, 48
+    p = orc.plan(Q, K, S, causal=False)
+    pc = orc.plan(Q, K, S, causal=True)
+    np.testing.assert_array_equal(p["q_perm"], pc["q_perm"])          # the query side is unchanged
+    np.testing.assert_allclose(p["q_mean"], pc["q_mean"])
+    for h in range(2):
+        for n in range(L // S):
+            row = p["kv_perm"][0, h, n * L:(n + 1) * L]
+            sk = p["s_k"][0, h, n * L:(n + 1) * L]
+            assert sorted(row.tolist()) == list(range(L))
+            np.testing.assert_allclose(sk, K[0, 0] @ Q[0, h, n * S:(n + 1) * S].mean(axis=0), atol=1e-12)
+            assert (np.diff(sk[row]) <= 0).all()
+            # restricted to the causal prefix, the order is the causal row's order
+            if n:
+                o = orc.kv_row_offset(n, S)
+                np.testing.assert_array_equal(row[row < n * S], pc["kv_perm"][0, h, o:o + n * S])
+
+
+@pytest.mark.parametrize("stop_mode,max_tiles", [(0, None), (1, None), (2, 3), (0, 4)])
+def test_noncausal_against_literal_model(stop_mode, max_tiles):
+    rng = np.random.default_rng(77)
+    L, D, S, BM, BN = 16, 2, 8, 4, 2
+    for trial in range(6):
+        Q = rng.choice([-1.0, 0.0, 1.5], size=(1, 1, L, D))
+        K = rng.choice([-1.0, 0.5, 1.0], size=(1, 1, L, D))
+        V = rng.standard_normal((1, 1, L, D))
+        scale = 0.7
+        p = orc.plan(Q, K, S, causal=False)
+        for tau in (0.0, 0.05, 0.2, 0.6):
+            O, c, s = orc.attention(Q, K, V, p["q_perm"], p["kv_perm"], S, BM, BN, tau, stop_mode=stop_mode,
+                                    scale=scale, max_tiles=max_tiles, causal=False)
+            ref, counts, maps = py_s2o_noncausal(Q[0, 0].tolist(), K[0, 0].tolist(), V[0, 0].tolist(), S, BM, BN,
+                                                 tau, stop_mode, max_tiles, scale)
+            for n, (qp, kvp) in enumerate(maps):
+                assert p["q_perm"][0, 0, n].tolist() == qp
+                assert p["kv_perm"][0, 0, n * L:(n + 1) * L].tolist() == kvp
+            np.testing.assert_allclose(O[0, 0], np.array(ref), rtol=0, atol=1e-12)
+            assert [(int(a), int(b)) for a, b in zip(c[0, 0], s[0, 0])] == counts
+
+
+@pytest.mark.parametrize("stop_mode", [0, 1])
+def test_noncausal_streaming_equals_visited_set_form(stop_mode):
+    Q, K, V = rand_qkv(1, 2, 1, 64, 8, scale=1.5)
+    S, BM, BN = 16, 8, 4
+    p = orc.plan(Q, K, S, causal=False)
+    stopped = 0
+    for tau in (0.0, 0.02, 0.1, 0.5):
+        a = orc.attention(Q, K, V, p["q_perm"], p["kv_perm"], S, BM, BN, tau, stop_mode=stop_mode, causal=False)
+        b = orc.attention_visited_set(Q, K, V, p["q_perm"], p["kv_perm"], S, BM, BN, tau, stop_mode=stop_mode,
+                                      causal=False)
+        np.testing.assert_allclose(a[0], b[0], rtol=0, atol=1e-11)
+        np.testing.assert_array_equal(a[1], b[1])
+        np.testing.assert_array_equal(a[2], b[2])
+        stopped += int((a[2] > 0).sum())
+        assert (a[1] >= 1).all()                       # the first tile is always kept
+    assert stopped > 0
