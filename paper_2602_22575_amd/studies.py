@@ -10,6 +10,10 @@
         D  + the early-stop vote, never stopping        (stop_mode 0, tau = -1)
       followed by B, C, D in the non-causal setting (params.non_causal: every query walks all
       L keys; there is no contiguous non-causal kernel, so no A).
+  python -m paper_2602_22575_amd.studies topk         fixed budget on the ranked order (the top-k
+      selection of the appendix's matched-sparsity comparison): non-causal walk without a
+      stop rule visiting the first k tiles of every ranked row, k = a fraction of L/64;
+      time and speed-up over the full walk against the ideal 1/fraction.
   python -m paper_2602_22575_amd.studies plan-table   ranking time over (L, S) (the paper's
       retrieval-latency table in "Additional details on end-to-end operator performance"),
       with time * S / L^2 to check the L^2 / S law.
@@ -119,6 +123,33 @@ def abcd():
         torch.cuda.empty_cache()
 
 
+def topk():
+    import torch
+    from . import binding as s2o, inputs
+    print("| L | kept fraction of key tiles | attention ms | speed-up over the full walk | ideal |")
+    print("|---|---|---|---|---|")
+    for name in ("llama32k", "llama128k"):
+        w = inputs.workload(name)
+        Qd, Kd, Vd = (_dev(x) for x in inputs.make_qkv(w))
+        O = torch.empty_like(Qd)
+        cnt = torch.empty((w.Z, w.H, w.L // w.BM), dtype=torch.int32, device="cuda:0")
+        cnt2 = torch.empty_like(cnt)
+        pp = s2o.make_params(w.Z, w.H, w.Hkv, w.L, w.D, w.S, w.BM, w.BN, stop_mode=2, non_causal=1)
+        plan = s2o.s2o_plan(Qd, Kd, pp, want_scores=False)
+        nK = w.L // w.BN
+        full = None
+        for frac in (1.0, 0.5, 0.25, 0.125, 0.0625, 0.03125):
+            k = max(1, int(round(frac * nK)))
+            p = s2o.make_params(w.Z, w.H, w.Hkv, w.L, w.D, w.S, w.BM, w.BN, stop_mode=2, non_causal=1,
+                                max_prefix_tiles=k)
+            ms = _timed(lambda: s2o.s2o_attention(Qd, Kd, Vd, p, plan.q_perm, plan.kv_perm, -1.0, O=O,
+                                                  computed=cnt, skipped=cnt2), 3)
+            full = ms if full is None else full
+            print(f"| {w.L} | {k / nK:.4f} | {ms:.2f} | {full / ms:.2f} | {nK / k:.2f} |", flush=True)
+        del Qd, Kd, Vd, O, plan
+        torch.cuda.empty_cache()
+
+
 def plan_table():
     import torch
     from . import binding as s2o, inputs
@@ -225,6 +256,8 @@ if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else ""
     if what == "abcd":
         abcd()
+    elif what == "topk":
+        topk()
     elif what == "plan-table":
         plan_table()
     elif what == "mixed":
