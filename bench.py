@@ -91,6 +91,7 @@ def main():
     ap.add_argument("--workload", default="llama128k")
     ap.add_argument("--tau", type=float, default=5e-3)
     ap.add_argument("--block-m", type=int, default=None, help="query tile rows (64 or 128); default: the workload's")
+    ap.add_argument("--seg-len", type=int, default=None, help="segment length S; default: the workload's (2048 at 128K)")
     ap.add_argument("--sweep", action="store_true", help="also time every tau of the workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mse", action="store_true")
@@ -115,7 +116,12 @@ def main():
         sys.exit(3)
     s2o.load_library()
     dev = torch.device("cuda:0")
-    w = inputs.workload(args.workload) if args.block_m is None else inputs.workload(args.workload, BM=args.block_m)
+    over = {}
+    if args.block_m is not None:
+        over["BM"] = args.block_m
+    if args.seg_len is not None:
+        over["S"] = args.seg_len
+    w = inputs.workload(args.workload, **over)
     t0 = time.time()
     Qb, Kb, Vb = inputs.make_qkv(w)
     t_gen = time.time() - t0
