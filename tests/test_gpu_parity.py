@@ -387,7 +387,34 @@ def test_llama8k(gpu):
                 assert err.max() <= parity.O_MAX_ABS
 
 
-def _sampled_case(name, plan_heads, attn_samples, taus, stop_mode=0, variants=(), **overrides):
+def _bench_step(w, Qd, Kd, Vd, tau):
+    """The step exactly as bench.py enqueues it: the ranking (no score outputs, maps written
+    into given buffers) on the current stream, the own-segment pass beside it on a second
+    stream, then the prefix walk.  Returns (q_perm, kv_perm, O bits, computed, skipped)."""
+    import torch
+    import paper_2602_22575_amd as s2o
+    p = gu.params_for(w)
+    dev = Qd.device
+    P = w.S * w.N * (w.N - 1) // 2
+    maps = (torch.empty((w.Z, w.H, w.N, w.S), dtype=torch.int32, device=dev),
+            torch.empty((w.Z, w.H, max(P, 4)), dtype=torch.int32, device=dev))
+    scratch = torch.empty(s2o.s2o_plan_sizes(p)["scratch"], dtype=torch.uint8, device=dev)
+    state = torch.empty(s2o.s2o_attention_sizes(p)["scratch"], dtype=torch.uint8, device=dev)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    fork = torch.cuda.Event()
+    fork.record(main)
+    side.wait_event(fork)
+    s2o.s2o_attention_local(Qd, Kd, Vd, p, scratch=state, stream=side)
+    join = torch.cuda.Event()
+    join.record(side)
+    plan = s2o.s2o_plan(Qd, Kd, p, want_scores=False, scratch=scratch, maps=maps)
+    main.wait_event(join)
+    O, c, s = s2o.s2o_attention_prefix(Qd, Kd, Vd, p, plan.q_perm, plan.kv_perm, tau, state)
+    torch.cuda.synchronize()
+    return plan.q_perm.cpu().numpy(), plan.kv_perm.cpu().numpy(), gu.bits_of(O), c.cpu().numpy(), s.cpu().numpy()
+
+
+def _sampled_case(name, plan_heads, attn_samples, taus, stop_mode=0, variants=(), bench_form=False, **overrides):
     """Full-size workload in the launch configuration bench.py times (all heads, whole
     sequence on the GPU); the oracle checks the plan on a few heads and the attention on a
     few (head, segment) pairs it can compute one by one."""
@@ -419,6 +446,12 @@ def _sampled_case(name, plan_heads, attn_samples, taus, stop_mode=0, variants=()
             st.pop("gains")
             _say(f"   head {h} segments {segs}:", st)
         _say("   mean density", float(orc.density(s, w.L, w.S, w.BM, w.BN).mean()))
+        if bench_form and tau == taus[0] and stop_mode == 0:
+            # the same step as bench.py enqueues it must give the same bits as the calls just checked
+            _say(f"case: {name} the step in bench.py's form (two streams, no score outputs), tau={tau}")
+            qp2, kp2, Ob2, c2, s2 = _bench_step(w, Qd, Kd, Vd, tau)
+            assert np.array_equal(qp2, pg["q_perm"]) and np.array_equal(kp2, pg["kv_perm"])
+            assert np.array_equal(Ob2, Ob) and np.array_equal(c2, c) and np.array_equal(s2, s)
     # further launch forms at the first threshold: (stop_mode, two launches?, tile budget)
     for sm, two_pass, budget in variants:
         tau = taus[0]
@@ -450,7 +483,8 @@ def test_llama128k_sampled(gpu):
     """The headline shape (128K): plan parity on two heads, attention parity on sampled
     (head, segment) pairs, at the threshold bench.py times and with skipping disabled on
     one short segment."""
-    _sampled_case("llama128k", plan_heads=[3, 20], attn_samples=[(3, [1, 21]), (20, [42])], taus=(5e-3,))
+    _sampled_case("llama128k", plan_heads=[3, 20], attn_samples=[(3, [1, 21]), (20, [42])], taus=(5e-3,),
+                  bench_form=True)
 
 
 def test_mixed128k_sampled(gpu):
