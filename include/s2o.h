@@ -132,7 +132,9 @@ int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* 
  *            is 1 when a triggering tile was loaded and discarded (stop_mode 0), else 0.
  *            Tiles beyond max_prefix_tiles count as skipped.  Either may be NULL.
  *            With non_causal the row of segment n lists L/B_N tiles (for every n, segment 0
- *            included), tau must be finite, and scratch is ignored.
+ *            included), tau must be finite, scratch is ignored, and kv_perm may be NULL: every
+ *            query tile then walks all keys in storage order without reading a map
+ *            (contiguous dense attention, the decomposition's kernel A).
  *   scratch  NULL: one fused launch (the own-segment window and the prefix walk share
  *            registers).  Otherwise a device buffer, 256-byte aligned, of at least the size
  *            s2o_attention_sizes reports (else S2O_ESCRATCH): the call is then

@@ -155,7 +155,10 @@ int attention_call(int passes, const void* Q, const void* K, const void* V, cons
   if (walk) {
     if (!O || misaligned(O, 16)) return S2O_EINVAL;
     if (params->use_q_perm && !q_perm) return S2O_EINVAL;
-    if ((s.N > 1 || s.nc) && (!kv_perm || misaligned(kv_perm, 16))) return S2O_EINVAL;
+    // causal: the prefix rows are needed as soon as a prefix exists; non-causal: NULL means
+    // "all keys in storage order" (contiguous dense attention, App. A kernel A)
+    if (!s.nc && s.N > 1 && !kv_perm) return S2O_EINVAL;
+    if (kv_perm && misaligned(kv_perm, 16)) return S2O_EINVAL;
     if (tau != tau) return S2O_EINVAL;
     if (s.nc && isinf(tau)) return S2O_EINVAL;   // the first tile's test would be inf * 0
   }

@@ -80,10 +80,15 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   uint32_t tokk[4], tokv[4];            // tokens of the next K tile and of the next V tile
   auto load_index = [&](int t) {        // tokk <- tile t (clamped); only called when ntiles > 0
     const int pt = min(t, ntiles - 1);
+    if (a.kv_perm) {
 #pragma unroll
-    for (int gi = 0; gi < 4; ++gi) {
-      const int tk = kvrow[(int64_t)pt * kBN + 16 * wave + 4 * gi + (lane >> 4)];
-      tokk[gi] = (uint32_t)min(max(tk, 0), a.L - 1);
+      for (int gi = 0; gi < 4; ++gi) {
+        const int tk = kvrow[(int64_t)pt * kBN + 16 * wave + 4 * gi + (lane >> 4)];
+        tokk[gi] = (uint32_t)min(max(tk, 0), a.L - 1);
+      }
+    } else {                            // no map (non-causal only): the keys in storage order
+#pragma unroll
+      for (int gi = 0; gi < 4; ++gi) tokk[gi] = (uint32_t)(pt * kBN + 16 * wave + 4 * gi + (lane >> 4));
     }
   };
   auto load_k = [&](int t) {            // K tile t (its tokens are in tokk) -> buffer t & 1

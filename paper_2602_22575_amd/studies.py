@@ -8,8 +8,8 @@
         B  + indexed gather with identity maps          (stop_mode 2)
         C  + ranked maps from s2o_plan                  (stop_mode 2)
         D  + the early-stop vote, never stopping        (stop_mode 0, tau = -1)
-      followed by B, C, D in the non-causal setting (params.non_causal: every query walks all
-      L keys; there is no contiguous non-causal kernel, so no A).
+      followed by the same four in the non-causal setting (params.non_causal: every query
+      walks all L keys; A is the walk without a key map).
   python -m paper_2602_22575_amd.studies topk         fixed budget on the ranked order (the top-k
       selection of the appendix's matched-sparsity comparison): non-causal walk without a
       stop rule visiting the first k tiles of every ranked row, k = a fraction of L/64;
@@ -92,8 +92,8 @@ def abcd():
         del Qd, Kd, Vd, O, state, plan, qi, ki
         torch.cuda.empty_cache()
     print()
-    print("| L | S | non-causal: B identity gather ms (TFLOP/s) | C ranked gather ms | D + stop vote ms | C/B | D/C |")
-    print("|---|---|---|---|---|---|---|")
+    print("| L | S | non-causal: A no map ms (TFLOP/s) | B identity gather ms | C ranked gather ms | D + stop vote ms | B/A | C/B | D/C |")
+    print("|---|---|---|---|---|---|---|---|---|")
     for name in ("llama8k", "llama32k", "llama128k"):
         w = inputs.workload(name)
         Qd, Kd, Vd = (_dev(x) for x in inputs.make_qkv(w))
@@ -109,16 +109,18 @@ def abcd():
         N = w.L // w.S
         qi = torch.arange(w.S, dtype=torch.int32, device="cuda:0").expand(w.Z, w.H, N, w.S).contiguous()
         ki = torch.arange(w.L, dtype=torch.int32, device="cuda:0").repeat(N).expand(w.Z, w.H, N * w.L).contiguous()
-        variants = [lambda: s2o.s2o_attention(Qd, Kd, Vd, p2, qi, ki, -1.0, **kw),
+        pa = s2o.make_params(w.Z, w.H, w.Hkv, w.L, w.D, w.S, w.BM, w.BN, stop_mode=2, non_causal=1, use_q_perm=0)
+        variants = [lambda: s2o.s2o_attention(Qd, Kd, Vd, pa, None, None, -1.0, **kw),
+                    lambda: s2o.s2o_attention(Qd, Kd, Vd, p2, qi, ki, -1.0, **kw),
                     lambda: s2o.s2o_attention(Qd, Kd, Vd, p2, plan.q_perm, plan.kv_perm, -1.0, **kw),
                     lambda: s2o.s2o_attention(Qd, Kd, Vd, p0, plan.q_perm, plan.kv_perm, -1.0, **kw)]
         times = [[] for _ in variants]
         for rep in range(3):
             for i, fn in enumerate(variants):
                 times[i].append(_timed(fn, 1))
-        b_, c, d = (float(np.median(t)) for t in times)
-        print(f"| {w.L} | {w.S} | {b_:.2f} ({flops / b_ / 1e9:.0f}) | {c:.2f} | {d:.2f} | {c / b_:.3f} | {d / c:.3f} |",
-              flush=True)
+        a_, b_, c, d = (float(np.median(t)) for t in times)
+        print(f"| {w.L} | {w.S} | {a_:.2f} ({flops / a_ / 1e9:.0f}) | {b_:.2f} | {c:.2f} | {d:.2f} | "
+              f"{b_ / a_:.3f} | {c / b_:.3f} | {d / c:.3f} |", flush=True)
         del Qd, Kd, Vd, O, plan, qi, ki
         torch.cuda.empty_cache()
 

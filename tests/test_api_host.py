@@ -115,14 +115,13 @@ def test_null_and_scratch_errors_come_before_any_hip_call(lib):
     assert lib.s2o_attention(*bad) == b.S2O_ESCRATCH
     bad = list(args); bad[10] = C.c_void_p(0x10010); bad[11] = 1 << 40
     assert lib.s2o_attention(*bad) == b.S2O_ESCRATCH
-    # non-causal setting: no own-segment pass, the threshold must be finite, kv_perm needed even for N = 1
+    # non-causal setting: no own-segment pass, the threshold must be finite
     pn = b.make_params(1, 4, 2, 1024, 128, 256, non_causal=1)
     assert lib.s2o_attention_local(fake, fake, fake, C.byref(pn), fake, 1 << 40, None) == b.S2O_EUNSUPPORTED
     nargs = list(args); nargs[3] = C.byref(pn)
     bad = list(nargs); bad[6] = C.c_float(float("inf"))
     assert lib.s2o_attention(*bad) == b.S2O_EINVAL
-    p1 = b.make_params(1, 4, 2, 256, 128, 256, non_causal=1)
-    bad = list(args); bad[3] = C.byref(p1); bad[5] = None
+    bad = list(nargs); bad[5] = C.c_void_p(0x10004)    # a map, but misaligned
     assert lib.s2o_attention(*bad) == b.S2O_EINVAL
     p.struct_size = 8
     assert lib.s2o_attention(*args) == b.S2O_EINVAL

@@ -540,6 +540,9 @@ def test_tiny_noncausal_plan_and_attention(tiny):
     Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, torch.from_numpy(qi).cuda(), torch.from_numpy(ki).cuda(), -1.0, 2,
                                 use_q_perm=0, non_causal=1)
     assert np.abs(parity.to_f64(Ob) - dense).max() <= parity.O_MAX_ABS
+    # no key map at all: the same walk in storage order, identical bits
+    Ob2, c2, s2 = gu.gpu_attention(w, Qd, Kd, Vd, None, None, -1.0, 2, use_q_perm=0, non_causal=1)
+    assert np.array_equal(Ob2, Ob) and np.array_equal(c2, c) and np.array_equal(s2, s)
 
 
 def test_llama8k_noncausal_sampled(gpu):
