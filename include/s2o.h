@@ -29,7 +29,7 @@
  *     H % Hkv == 0 and query head h reads KV head h / (H/Hkv) (grouped-query attention).
  *   - Segments: N = L / S.  Packed prefix rows: for one (z,h) the KV_perm (and s_k) array
  *     has S*N*(N-1)/2 entries; row n (1 <= n < N, length n*S) starts at S*n*(n-1)/2.
- *     Segment 0 has no prefix.
+ *     Segment 0 has no prefix.  (params.non_causal changes this: see s2o_params.)
  */
 #ifndef S2O_H_
 #define S2O_H_
@@ -156,7 +156,9 @@ int s2o_attention_local(const void* Q, const void* K, const void* V, const s2o_p
 
 /* Pass 2 alone (Alg. 3; Alg. 4's walk when use_q_perm == 0): resumes each row from the state
  * s2o_attention_local left in `scratch` (read only; the caller orders the two calls), walks
- * the prefix as described under s2o_attention, normalises and writes O and the counts. */
+ * the prefix as described under s2o_attention, normalises and writes O and the counts.
+ * With params.non_causal there is no state: scratch is ignored (may be NULL) and the call is
+ * the same as s2o_attention; s2o_attention_local then returns S2O_EUNSUPPORTED. */
 int s2o_attention_prefix(const void* Q, const void* K, const void* V, const s2o_params* params,
                          const int32_t* q_perm, const int32_t* kv_perm, float tau, void* O,
                          int32_t* computed, int32_t* skipped, const void* scratch, size_t scratch_bytes,
