@@ -414,10 +414,15 @@ def _bench_step(w, Qd, Kd, Vd, tau):
     return plan.q_perm.cpu().numpy(), plan.kv_perm.cpu().numpy(), gu.bits_of(O), c.cpu().numpy(), s.cpu().numpy()
 
 
-def _sampled_case(name, plan_heads, attn_samples, taus, stop_mode=0, variants=(), bench_form=False, **overrides):
+def _sampled_case(name, plan_heads, attn_samples, taus, stop_mode=0, variants=(), bench_form=False,
+                  more_taus=(), dense_sample=None, **overrides):
     """Full-size workload in the launch configuration bench.py times (all heads, whole
     sequence on the GPU); the oracle checks the plan on a few heads and the attention on a
-    few (head, segment) pairs it can compute one by one."""
+    few (head, segment) pairs it can compute one by one.
+    more_taus: (tau, sample indices) pairs -- further thresholds checked on a subset of
+    attn_samples, re-using the oracle's gain profiles of the first pass.
+    dense_sample: (head, segment) -- skipping disabled (tau = 0) on the whole workload, counts
+    checked everywhere and O of that segment against the dense definition."""
     w = inputs.workload(name, **overrides)
     _say(f"case: {name} {overrides} generate L={w.L}")
     Qb, Kb, Vb = inputs.make_qkv(w)
@@ -433,18 +438,29 @@ def _sampled_case(name, plan_heads, attn_samples, taus, stop_mode=0, variants=()
     _say(f"case: {name} oracle plan on heads {plan_heads}")
     stats = parity.check_plan(w, Qb, Kb, pg, heads=plan_heads)
     _say("  plan stats", stats)
+    tot = orc.prefix_tiles(w.L, w.S, w.BM, w.BN)[None, None]
+    gain_cache = {}
+
+    def check_samples(tau, Ob, c, s, which, sm=stop_mode, budget=0):
+        for i in which:
+            h, segs = attn_samples[i]
+            key = (i, sm)
+            st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, sm, Ob, c, s,
+                                        heads=[h], segments=segs, gains=gain_cache.get(key), max_tiles=budget)
+            g = st.pop("gains", None)
+            if g:
+                gain_cache[key] = g
+            _say(f"   head {h} segments {segs}:", st)
+            # knife-edge stop decisions (inside the guard band) must stay rare
+            assert st["ambiguous"] <= 0.02 * (st["robust"] + st["ambiguous"]) + 1, st
+
     for tau in taus:
         _say(f"case: {name} attention tau={tau}")
         Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, stop_mode)
-        tot = orc.prefix_tiles(w.L, w.S, w.BM, w.BN)[None, None]
         assert np.all((c >= 0) & (s >= 0) & (tot - c - s >= 0) & (tot - c - s <= 1))
         if tau <= 0:
             assert np.all(s == 0) and np.all(c == tot)
-        for h, segs in attn_samples:
-            st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, stop_mode, Ob, c, s,
-                                        heads=[h], segments=segs)
-            st.pop("gains")
-            _say(f"   head {h} segments {segs}:", st)
+        check_samples(tau, Ob, c, s, range(len(attn_samples)))
         _say("   mean density", float(orc.density(s, w.L, w.S, w.BM, w.BN).mean()))
         if bench_form and tau == taus[0] and stop_mode == 0:
             # the same step as bench.py enqueues it must give the same bits as the calls just checked
@@ -452,17 +468,31 @@ def _sampled_case(name, plan_heads, attn_samples, taus, stop_mode=0, variants=()
             qp2, kp2, Ob2, c2, s2 = _bench_step(w, Qd, Kd, Vd, tau)
             assert np.array_equal(qp2, pg["q_perm"]) and np.array_equal(kp2, pg["kv_perm"])
             assert np.array_equal(Ob2, Ob) and np.array_equal(c2, c) and np.array_equal(s2, s)
+    for tau, which in more_taus:
+        _say(f"case: {name} attention tau={tau} on samples {list(which)}")
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, stop_mode)
+        assert np.all((c >= 0) & (s >= 0) & (tot - c - s >= 0) & (tot - c - s <= 1))
+        check_samples(tau, Ob, c, s, which)
+        _say("   mean density", float(orc.density(s, w.L, w.S, w.BM, w.BN).mean()))
+    if dense_sample is not None:
+        h, n = dense_sample
+        _say(f"case: {name} attention tau=0 (no skipping), O of head {h} segment {n} against the dense definition")
+        Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, 0.0, stop_mode)
+        assert np.all(s == 0) and np.all(c == tot)
+        g = h // w.G
+        rows = np.arange(n * w.S, (n + 1) * w.S)
+        d = orc.dense_attention(parity.to_f64(Qb[:, h:h + 1]), parity.to_f64(Kb[:, g:g + 1]),
+                                parity.to_f64(Vb[:, g:g + 1]), rows=rows)
+        err = np.abs(parity.to_f64(Ob[0, h, rows]) - d[0, 0])
+        _say("   max-abs", float(err.max()), "rel mse", float((err ** 2).sum() / (d ** 2).sum()))
+        assert err.max() <= parity.O_MAX_ABS and (err ** 2).sum() / (d ** 2).sum() <= parity.O_REL_MSE
     # further launch forms at the first threshold: (stop_mode, two launches?, tile budget)
     for sm, two_pass, budget in variants:
         tau = taus[0]
         _say(f"case: {name} attention tau={tau} stop_mode={sm} two_pass={two_pass} budget={budget}")
         Ob, c, s = gu.gpu_attention(w, Qd, Kd, Vd, plan.q_perm, plan.kv_perm, tau, sm, two_pass=two_pass,
                                     max_tiles=budget)
-        for h, segs in attn_samples:
-            st = parity.check_attention(w, Qb, Kb, Vb, pg["q_perm"], pg["kv_perm"], tau, sm, Ob, c, s,
-                                        heads=[h], segments=segs, max_tiles=budget)
-            st.pop("gains", None)
-            _say(f"   head {h} segments {segs}:", st)
+        check_samples(tau, Ob, c, s, range(len(attn_samples)), sm=sm, budget=budget)
 
 
 def test_llama32k_sampled(gpu):
@@ -480,18 +510,25 @@ def test_llama32k_other_segment_lengths(gpu, S):
 
 
 def test_llama128k_sampled(gpu):
-    """The headline shape (128K): plan parity on two heads, attention parity on sampled
-    (head, segment) pairs, at the threshold bench.py times and with skipping disabled on
-    one short segment."""
-    _sampled_case("llama128k", plan_heads=[3, 20], attn_samples=[(3, [1, 21]), (20, [42])], taus=(5e-3,),
-                  bench_form=True)
+    """The headline shape (128K): plan parity on four heads (one per second KV group); stop sets
+    and O on heads {0, 9, 18, 27} x segments {1, 21, 42, 63} (shortest to longest prefix) at the
+    threshold bench.py times, in bench.py's launch form too; two further thresholds of the
+    sweep (1e-4 and 2e-2) on four of those pairs; and skipping disabled (tau = 0) with O of
+    one short segment against the dense definition."""
+    heads, segs = [0, 9, 18, 27], [1, 21, 42, 63]
+    _sampled_case("llama128k", plan_heads=heads, attn_samples=[(h, [n]) for h in heads for n in segs],
+                  taus=(5e-3,), bench_form=True,
+                  more_taus=((1e-4, (1, 7, 10, 12)), (2e-2, (1, 7, 10, 12))),
+                  dense_sample=(0, 1))
 
 
 def test_mixed128k_sampled(gpu):
     """128K with half the KV groups unstructured (stopping rarely fires) and half strongly
-    structured, for both query tile shapes (64x64 and 128x64)."""
-    _sampled_case("mixed128k", plan_heads=[2, 29], attn_samples=[(2, [3]), (29, [40])], taus=(5e-3,))
-    _sampled_case("mixed128k", plan_heads=[], attn_samples=[(2, [3]), (29, [40])], taus=(5e-3,), BM=128)
+    structured, for both query tile shapes (64x64 and 128x64): one unstructured head (2) and
+    one boosted head (29), each on segments 3, 40 and 63."""
+    samples = [(h, [n]) for h in (2, 29) for n in (3, 40, 63)]
+    _sampled_case("mixed128k", plan_heads=[2, 29], attn_samples=samples, taus=(5e-3,))
+    _sampled_case("mixed128k", plan_heads=[], attn_samples=samples, taus=(5e-3,), BM=128)
 
 
 # ---------------------------------------------------------------- non-causal setting

@@ -375,6 +375,46 @@ def test_local_window_only_sparsity_matches_paper_table3():
     assert abs(1 - orc.density(skip, L, S, B, B)[0, 0] - sparsity) < 1e-15
 
 
+def _brute_blocks(L, S, BM, BN):
+    """Brute force on the explicit L x L causal mask: B_M x B_N score blocks that hold at least
+    one causal element (key <= query), split into blocks of the query's own segment and blocks
+    of earlier segments (the prefix), per query block."""
+    i, j = np.arange(L)[:, None], np.arange(L)[None, :]
+    mask = j <= i
+    own = np.zeros(L // BM, dtype=np.int64)
+    pre = np.zeros(L // BM, dtype=np.int64)
+    for b in range(L // BM):
+        for t in range(L // BN):
+            if mask[b * BM:(b + 1) * BM, t * BN:(t + 1) * BN].any():
+                if (t * BN) // S == (b * BM) // S:
+                    own[b] += 1
+                else:
+                    pre[b] += 1
+    return own, pre
+
+
+@pytest.mark.parametrize("L,S,BM,BN", [(64, 16, 8, 4), (96, 32, 16, 4), (512, 256, 128, 64), (1024, 256, 128, 64),
+                                       (64, 16, 4, 4)])
+def test_density_for_unequal_tile_shapes_matches_brute_force_block_count(L, S, BM, BN):
+    """density() in units of B_M x B_N score blocks when B_M != B_N (the 128x64 tiling):
+    every block that contains a causal element counts whole; checked against a count on the
+    explicit mask, with nothing skipped, everything skipped and random skip counts."""
+    own, pre = _brute_blocks(L, S, BM, BN)
+    assert np.array_equal(pre, orc.prefix_tiles(L, S, BM, BN))
+    total = own.sum() + pre.sum()
+    rng = np.random.default_rng(L + BM)
+    zero = np.zeros((1, 2, L // BM), dtype=np.int64)
+    assert np.all(orc.density(zero, L, S, BM, BN) == 1.0)
+    allskip = np.broadcast_to(pre, zero.shape)
+    np.testing.assert_allclose(orc.density(allskip, L, S, BM, BN), own.sum() / total, rtol=0, atol=1e-15)
+    for _ in range(5):
+        skip = rng.integers(0, pre + 1, size=zero.shape)
+        want = (own.sum() + (pre[None, None] - skip).sum(axis=-1)) / total
+        np.testing.assert_allclose(orc.density(skip, L, S, BM, BN), want, rtol=0, atol=1e-15)
+    if BM == BN:
+        assert own.sum() == orc.pass1_tiles(L, S, BM) and total == orc.causal_tiles(L, BM)
+
+
 def test_bf16_conversions_roundtrip():
     bits = np.arange(0, 1 << 16, dtype=np.uint32).astype(np.uint16)
     vals = orc.bf16_bits_to_f64(bits)
