@@ -25,7 +25,9 @@
  *   - Return value: S2O_OK (0) or a negative code.  On an argument error nothing is
  *     enqueued and nothing is written.
  *   - Tensors: Q [Z,H,L,D], K and V [Z,Hkv,L,D], O [Z,H,L,D]; bf16; the last dimension is
- *     contiguous; the other strides are given in elements (0 = packed default).
+ *     contiguous; the other strides are given in elements (0 = packed default), multiples
+ *     of 8.  One K or V head must span less than 4 GiB ((L-1) * row stride in bytes + 256
+ *     < 2^32, row stride < 16 MiB; else S2O_EUNSUPPORTED).
  *     H % Hkv == 0 and query head h reads KV head h / (H/Hkv) (grouped-query attention).
  *   - Segments: N = L / S.  Packed prefix rows: for one (z,h) the KV_perm (and s_k) array
  *     has S*N*(N-1)/2 entries; row n (1 <= n < N, length n*S) starts at S*n*(n-1)/2.
@@ -41,7 +43,7 @@
 extern "C" {
 #endif
 
-#define S2O_VERSION 3
+#define S2O_VERSION 4
 
 enum {
   S2O_OK = 0,
@@ -93,7 +95,19 @@ typedef struct s2o_plan_out {
                                                                             (Eq. (2)), or NULL */
   float* q_mean;     /* [Z,H,N,D]  segment means of Q, or NULL                             */
   float* k_guide;    /* [Z,Hkv,D]  mean of the first key segment, or NULL                  */
+  int32_t* status;   /* one int32 (device), or NULL: 0 after a plan whose internal invariants all
+                        held, else a mask of S2O_PLAN_* bits -- KV_perm is then not to be trusted.
+                        The bits can only be set by a defect of the library or by NaN scores;
+                        they exist so that such a plan cannot pass for a good one.           */
 } s2o_plan_out;
+
+/* bits of *s2o_plan_out.status */
+enum {
+  S2O_PLAN_STAGE_OVERFLOW = 1,  /* a bucket received more keys than were counted for it       */
+  S2O_PLAN_COUNT_MISMATCH = 2,  /* a row's bucket counts do not add up to its length          */
+  S2O_PLAN_SPAN_OVERFLOW = 4,   /* more sort spans than the scratch buffer has room for       */
+  S2O_PLAN_BAD_RANK = 8         /* a key was ranked outside its row                           */
+};
 
 int s2o_version(void);
 const char* s2o_strerror(int code);

@@ -31,7 +31,8 @@ class S2OParams(C.Structure):
 
 class S2OPlanOut(C.Structure):
     _fields_ = [("q_perm", C.c_void_p), ("kv_perm", C.c_void_p), ("s_q", C.c_void_p),
-                ("s_k", C.c_void_p), ("q_mean", C.c_void_p), ("k_guide", C.c_void_p)]
+                ("s_k", C.c_void_p), ("q_mean", C.c_void_p), ("k_guide", C.c_void_p),
+                ("status", C.c_void_p)]
 
 
 class S2OError(RuntimeError):
@@ -121,6 +122,38 @@ def _ptr(t) -> Optional[int]:
     return None if t is None else t.data_ptr()
 
 
+def _check_qkv(params: S2OParams, **tensors):
+    """The library sees only pointers: refuse tensors it would silently misread (wrong dtype,
+    another device, or a memory layout that params' strides do not describe)."""
+    import torch
+    dev = None
+    for name, t in tensors.items():
+        if t is None:
+            continue
+        if t.dtype != torch.bfloat16 or not t.is_cuda:
+            raise ValueError(f"{name}: expected a CUDA bfloat16 tensor, got {t.dtype} on {t.device}")
+        dev = t.device if dev is None else dev
+        if t.device != dev:
+            raise ValueError(f"{name}: on {t.device}, the other tensors on {dev}")
+        stride = tuple(getattr(params, {"Q": "q_stride", "K": "k_stride", "V": "v_stride", "O": "o_stride"}[name]))
+        if stride == (0, 0, 0):
+            if not t.is_contiguous():
+                raise ValueError(f"{name}: params describe a packed [Z,heads,L,D] tensor but this one is not "
+                                 "contiguous (pass its strides in params or call .contiguous())")
+        elif t.stride(-1) != 1:
+            raise ValueError(f"{name}: the last dimension must be contiguous")
+
+
+def _keep_alive_on(stream, *tensors):
+    """Buffers allocated here and handed to kernels on a stream other than torch's current one
+    must not be recycled by the caching allocator before that stream has passed them."""
+    if stream is None:
+        return
+    for t in tensors:
+        if t is not None:
+            t.record_stream(stream)
+
+
 def _stream_handle(stream) -> Optional[int]:
     import torch
     s = torch.cuda.current_stream() if stream is None else stream
@@ -135,6 +168,7 @@ class Plan:
     s_k: "object" = None
     q_mean: "object" = None
     k_guide: "object" = None
+    status: "object" = None      # int32[1] on the device: 0, or S2O_PLAN_* bits (see s2o.h)
 
 
 def s2o_plan(Q, K, params: S2OParams, want_scores: bool = True, scratch=None, stream=None,
@@ -145,6 +179,7 @@ def s2o_plan(Q, K, params: S2OParams, want_scores: bool = True, scratch=None, st
     (P = entries of the key rows of one head: S*N(N-1)/2, or N*L when params.non_causal)."""
     import torch
     lib = load_library()
+    _check_qkv(params, Q=Q, K=K)
     sz = s2o_plan_sizes(params)
     dev = Q.device
     Z, H, Hkv, L, D, S = (params.batch, params.q_heads, params.kv_heads, params.seq_len,
@@ -164,10 +199,14 @@ def s2o_plan(Q, K, params: S2OParams, want_scores: bool = True, scratch=None, st
         out.s_k = torch.empty((Z, H, max(P, 4)), dtype=torch.float32, device=dev)
         out.q_mean = torch.empty((Z, H, N, D), dtype=torch.float32, device=dev)
         out.k_guide = torch.empty((Z, Hkv, D), dtype=torch.float32, device=dev)
-    if scratch is None:
+    own_scratch = scratch is None
+    if own_scratch:
         scratch = torch.empty(sz["scratch"], dtype=torch.uint8, device=dev)
+    out.status = torch.empty(1, dtype=torch.int32, device=dev)
+    _keep_alive_on(stream, scratch if own_scratch else None, out.status, out.s_q, out.s_k, out.q_mean, out.k_guide,
+                   None if maps is not None else out.q_perm, None if maps is not None else out.kv_perm)
     po = S2OPlanOut(_ptr(out.q_perm), _ptr(out.kv_perm), _ptr(out.s_q), _ptr(out.s_k),
-                    _ptr(out.q_mean), _ptr(out.k_guide))
+                    _ptr(out.q_mean), _ptr(out.k_guide), _ptr(out.status))
     _check(lib.s2o_plan(Q.data_ptr(), K.data_ptr(), C.byref(params), C.byref(po),
                         scratch.data_ptr(), scratch.numel(), _stream_handle(stream)))
     if P == 0:
@@ -189,19 +228,26 @@ def s2o_attention(Q, K, V, params: S2OParams, q_perm, kv_perm, tau: float, O=Non
     given); False: one fused launch."""
     import torch
     lib = load_library()
+    _check_qkv(params, Q=Q, K=K, V=V, O=O)
     sz = s2o_attention_sizes(params)
     dev = Q.device
     Z, H, L, D = params.batch, params.q_heads, params.seq_len, params.head_dim
+    fresh = []
     if O is None:
         O = torch.empty((Z, H, L, D), dtype=torch.bfloat16, device=dev)
+        fresh.append(O)
     if computed is None:
         computed = torch.empty((Z, H, L // params.block_m), dtype=torch.int32, device=dev)
+        fresh.append(computed)
     if skipped is None:
         skipped = torch.empty((Z, H, L // params.block_m), dtype=torch.int32, device=dev)
+        fresh.append(skipped)
     if two_pass and scratch is None and sz["scratch"] > 0:
         scratch = torch.empty(sz["scratch"], dtype=torch.uint8, device=dev)
+        fresh.append(scratch)
     if not two_pass:
         scratch = None
+    _keep_alive_on(stream, *fresh)
     _check(lib.s2o_attention(Q.data_ptr(), K.data_ptr(), V.data_ptr(), C.byref(params),
                              _ptr(q_perm), _ptr(kv_perm), float(tau), O.data_ptr(),
                              computed.data_ptr(), skipped.data_ptr(), _ptr(scratch),
@@ -213,8 +259,10 @@ def s2o_attention_local(Q, K, V, params: S2OParams, scratch=None, stream=None):
     """Pass 1 (Alg. 2) alone.  Returns the state buffer (uint8 tensor) s2o_attention_prefix reads."""
     import torch
     lib = load_library()
+    _check_qkv(params, Q=Q, K=K, V=V)
     if scratch is None:
         scratch = torch.empty(s2o_attention_sizes(params)["scratch"], dtype=torch.uint8, device=Q.device)
+        _keep_alive_on(stream, scratch)
     _check(lib.s2o_attention_local(Q.data_ptr(), K.data_ptr(), V.data_ptr(), C.byref(params),
                                    scratch.data_ptr(), scratch.numel(), _stream_handle(stream)))
     return scratch
@@ -226,14 +274,20 @@ def s2o_attention_prefix(Q, K, V, params: S2OParams, q_perm, kv_perm, tau: float
     (None when params.non_causal: there is no state)."""
     import torch
     lib = load_library()
+    _check_qkv(params, Q=Q, K=K, V=V, O=O)
     dev = Q.device
     Z, H, L, D = params.batch, params.q_heads, params.seq_len, params.head_dim
+    fresh = []
     if O is None:
         O = torch.empty((Z, H, L, D), dtype=torch.bfloat16, device=dev)
+        fresh.append(O)
     if computed is None:
         computed = torch.empty((Z, H, L // params.block_m), dtype=torch.int32, device=dev)
+        fresh.append(computed)
     if skipped is None:
         skipped = torch.empty((Z, H, L // params.block_m), dtype=torch.int32, device=dev)
+        fresh.append(skipped)
+    _keep_alive_on(stream, *fresh)
     _check(lib.s2o_attention_prefix(Q.data_ptr(), K.data_ptr(), V.data_ptr(), C.byref(params),
                                     _ptr(q_perm), _ptr(kv_perm), float(tau), O.data_ptr(),
                                     computed.data_ptr(), skipped.data_ptr(), _ptr(scratch),

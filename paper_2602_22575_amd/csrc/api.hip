@@ -51,6 +51,7 @@ int check_params(const s2o_params* p, Shape* s, bool for_plan = false) {
   if ((p->block_m != 64 && p->block_m != 128) || p->block_n != 64) return S2O_EUNSUPPORTED;
   if (p->seg_len % p->block_m != 0) return S2O_EUNSUPPORTED;
   if (for_plan && p->seg_len > 8192) return S2O_EUNSUPPORTED;   // a segment's query scores are sorted in LDS
+  if (for_plan && p->seq_len > (1 << 20)) return S2O_EUNSUPPORTED;   // a row's sample (L/64 scores) is sorted in LDS
   if ((int64_t)p->batch * p->q_heads * (p->seq_len / p->seg_len) > (1 << 24)) return S2O_EUNSUPPORTED;
   s->Z = p->batch; s->H = p->q_heads; s->Hkv = p->kv_heads; s->L = p->seq_len;
   s->D = p->head_dim; s->S = p->seg_len; s->N = p->seq_len / p->seg_len; s->nc = p->non_causal;
@@ -58,10 +59,43 @@ int check_params(const s2o_params* p, Shape* s, bool for_plan = false) {
   if (!fill_strides(p->k_stride, s->ks, s->Hkv, s->L, s->D)) return S2O_EINVAL;
   if (!fill_strides(p->v_stride, s->vs, s->Hkv, s->L, s->D)) return S2O_EINVAL;
   if (!fill_strides(p->o_stride, s->os, s->H, s->L, s->D)) return S2O_EINVAL;
+  // the prefix walk addresses a K/V row as a 32-bit byte offset from its head (24-bit multiply)
+  for (const int64_t* st : {s->ks, s->vs}) {
+    const int64_t row_bytes = st[2] * 2;
+    if (row_bytes >= (1 << 24) || (int64_t)(s->L - 1) * row_bytes + 256 > 0xffffffffll) return S2O_EUNSUPPORTED;
+  }
+  if (s->L > (1 << 24)) return S2O_EUNSUPPORTED;
   return S2O_OK;
 }
 
 bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+int plan_call(const void* Q, const void* K, const s2o_params* params, const s2o_plan_out* out, void* scratch,
+              size_t scratch_bytes, void* stream) {
+  Shape s;
+  const int rc = check_params(params, &s, true);
+  if (rc != S2O_OK) return rc;
+  if (!Q || !K || !out || !out->q_perm) return S2O_EINVAL;
+  if ((s.N > 1 || s.nc) && !out->kv_perm) return S2O_EINVAL;
+  if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(out->q_perm, 16) ||
+      misaligned(out->kv_perm, 16) || misaligned(out->s_k, 16) || misaligned(out->status, 4))
+    return S2O_EINVAL;
+  const size_t need = s2o::plan_scratch_bytes(s.Z, s.H, s.Hkv, s.L, s.S, s.nc);
+  if (!scratch || misaligned(scratch, 256) || scratch_bytes < need) return S2O_ESCRATCH;
+
+  s2o::PlanArgs a;
+  memset(&a, 0, sizeof(a));
+  a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K;
+  a.q_perm = out->q_perm; a.kv_perm = out->kv_perm;
+  a.s_q = out->s_q; a.s_k = out->s_k; a.q_mean = out->q_mean; a.k_guide = out->k_guide;
+  a.status = out->status;
+  a.Z = s.Z; a.H = s.H; a.Hkv = s.Hkv; a.L = s.L; a.S = s.S; a.N = s.N;
+  a.non_causal = s.nc;
+  for (int i = 0; i < 3; ++i) { a.qs[i] = s.qs[i]; a.ks[i] = s.ks[i]; }
+  a.scratch = scratch; a.scratch_bytes = scratch_bytes;
+  const hipError_t e = s2o::launch_plan(a, (hipStream_t)stream);
+  return e == hipSuccess ? S2O_OK : hip_fail(e);
+}
 
 }  // namespace
 
@@ -102,28 +136,7 @@ int s2o_plan_sizes(const s2o_params* params, size_t* q_perm_bytes, size_t* kv_pe
 
 int s2o_plan(const void* Q, const void* K, const s2o_params* params, const s2o_plan_out* out,
              void* scratch, size_t scratch_bytes, void* stream) {
-  Shape s;
-  const int rc = check_params(params, &s, true);
-  if (rc != S2O_OK) return rc;
-  if (!Q || !K || !out || !out->q_perm) return S2O_EINVAL;
-  if ((s.N > 1 || s.nc) && !out->kv_perm) return S2O_EINVAL;
-  if (misaligned(Q, 16) || misaligned(K, 16) || misaligned(out->q_perm, 16) ||
-      misaligned(out->kv_perm, 16) || misaligned(out->s_k, 16))
-    return S2O_EINVAL;
-  const size_t need = s2o::plan_scratch_bytes(s.Z, s.H, s.Hkv, s.L, s.S, s.nc);
-  if (!scratch || misaligned(scratch, 256) || scratch_bytes < need) return S2O_ESCRATCH;
-
-  s2o::PlanArgs a;
-  memset(&a, 0, sizeof(a));
-  a.Q = (const uint16_t*)Q; a.K = (const uint16_t*)K;
-  a.q_perm = out->q_perm; a.kv_perm = out->kv_perm;
-  a.s_q = out->s_q; a.s_k = out->s_k; a.q_mean = out->q_mean; a.k_guide = out->k_guide;
-  a.Z = s.Z; a.H = s.H; a.Hkv = s.Hkv; a.L = s.L; a.S = s.S; a.N = s.N;
-  a.non_causal = s.nc;
-  for (int i = 0; i < 3; ++i) { a.qs[i] = s.qs[i]; a.ks[i] = s.ks[i]; }
-  a.scratch = scratch; a.scratch_bytes = scratch_bytes;
-  const hipError_t e = s2o::launch_plan(a, (hipStream_t)stream);
-  return e == hipSuccess ? S2O_OK : hip_fail(e);
+  return plan_call(Q, K, params, out, scratch, scratch_bytes, stream);
 }
 
 int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* scratch_bytes) {

@@ -37,6 +37,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace s2o {
 namespace tile {
 
@@ -160,6 +162,228 @@ __device__ __forceinline__ void pv_tile(const uint16_t* vt, const Operands& op, 
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Explicitly scheduled operand reads (used by local.hip and prefix.hip).
+//
+// The compiler cannot tell an LDS read of one tile buffer from the asynchronous global->LDS
+// load that is filling another, so it drains every outstanding global load (s_waitcnt
+// vmcnt(0)) before any LDS read it knows about: a tile fetch issued at the top of a step
+// would be waited for at the step's first operand read, with the whole memory latency
+// exposed.  The operand reads below are therefore issued from inline assembly, which the
+// compiler's wait insertion does not look into, and every fragment is handed to its MFMA
+// through an explicit `s_waitcnt lgkmcnt(n)` that names how many younger LDS reads may still be
+// in flight (LDS reads complete in order).  The kernels wait for their own tile fetches
+// themselves (wait_tile_loads) right before the barrier that publishes a tile.
+//
+// Addresses: one VGPR per fragment slot (the swizzle makes them lane-dependent), fixed for the
+// whole kernel; tile buffer and sub-block are selected with the instruction's immediate offset.
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_t)(uintptr_t)(lvoid*)p; }
+
+template <int kOff>
+__device__ __forceinline__ void lds_issue_b128(bf16x8& d, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(kOff) : "memory");
+}
+template <int kOff>
+__device__ __forceinline__ void lds_issue_tr64(u32x2& d, uint32_t addr) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(kOff) : "memory");
+}
+// The same reads at address (addr ^ kXor): the XOR stays next to its read (a separate statement
+// would be hoisted out of the loop and cost the register it was meant to save).
+template <int kOff, int kXor>
+__device__ __forceinline__ void lds_issue_b128_x2(bf16x8& d0, bf16x8& d1, uint32_t addr) {   // two reads, 32 rows apart
+  if constexpr (kXor == 0) {
+    asm volatile("ds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4"
+                 : "=&v"(d0), "=&v"(d1) : "v"(addr), "n"(kOff), "n"(kOff + kTileElems) : "memory");
+  } else {
+    uint32_t t;
+    asm volatile("v_xor_b32 %2, %5, %3\n\tds_read_b128 %0, %2 offset:%4\n\tds_read_b128 %1, %2 offset:%6"
+                 : "=&v"(d0), "=&v"(d1), "=&v"(t) : "v"(addr), "n"(kOff), "n"(kXor), "n"(kOff + kTileElems) : "memory");
+  }
+}
+template <int kOff, int kXor>
+__device__ __forceinline__ void lds_issue_tr64_x(u32x2& d, uint32_t addr) {
+  if constexpr (kXor == 0) {
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(kOff) : "memory");
+  } else {
+    uint32_t t;
+    asm volatile("v_xor_b32 %1, %4, %2\n\tds_read_b64_tr_b16 %0, %1 offset:%3"
+                 : "=&v"(d), "=&v"(t) : "v"(addr), "n"(kOff), "n"(kXor) : "memory");
+  }
+}
+// The named values are valid once at most kYounger LDS reads issued after them are outstanding.
+template <int kYounger>
+__device__ __forceinline__ void lds_wait(bf16x8& a, bf16x8& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(kYounger));
+}
+template <int kYounger>
+__device__ __forceinline__ void lds_wait(u32x2& a, u32x2& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(kYounger));
+}
+// Small reads issued among the fragment reads (stop votes, token indices): issue now, claim
+// when at most kYounger reads issued after them may still be in flight.
+__device__ __forceinline__ void lds_issue_word4(u32x4& d, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1" : "=v"(d) : "v"(addr) : "memory");
+}
+__device__ __forceinline__ void lds_issue_word(uint32_t& d, uint32_t addr) {
+  asm volatile("ds_read_b32 %0, %1" : "=v"(d) : "v"(addr) : "memory");
+}
+template <int kYounger>
+__device__ __forceinline__ void lds_wait(u32x4& a) { asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(kYounger)); }
+template <int kYounger>
+__device__ __forceinline__ void lds_wait(uint32_t& a) { asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(kYounger)); }
+// All global->LDS tile loads (and every other global load) of this wavefront have landed.
+__device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Byte addresses of a lane's operand fragments inside a tile that starts at LDS address `base`
+// (a multiple of 256).  The swizzle is an XOR on the 16-byte chunk index, i.e. on address bits
+// 4..7, so the eight K slots and the second V half follow from one register each by an XOR
+// with a constant (one VALU instruction at the point of use instead of a register held
+// through the kernel): K step kk = k0 ^ (kk << 5); V half 1 = (v[db] ^ 16) + 8 rows.
+struct OperandAddr {
+  uint32_t k0;        // K operand of contraction step 0, key block 0 (block 1: + 32 rows)
+  uint32_t v[4];      // V^T operand: [32-dim block], keys 0..7 of a 16-key step (next step: + 16 rows)
+  __device__ __forceinline__ void init(int lane, uint32_t base) {
+    Operands op;
+    op.init(lane);
+    k0 = base + 2u * (uint32_t)op.koff[0];
+#pragma unroll
+    for (int db = 0; db < 4; ++db) v[db] = base + 2u * (uint32_t)op.voff[db][0];
+  }
+};
+
+constexpr int kTileBytes = kTileElems * 2;          // 16 KB
+constexpr int kHalfTileBytes = kTileBytes / 2;      // key block 1 of a K tile
+constexpr int kVStepBytes = 16 * kRowElems * 2;     // one 16-key contraction step of a V tile
+
+// The 16 K-fragment reads and 32 V^T-fragment reads of one step form one issue sequence
+// (K read r = 2*kk + nb, then V read 16 + 2*(4*st + db) + half), so that the first V fragments
+// are already on their way while the last score MFMAs run:
+//   the K reads of kk = 0..kKAhead-1 up front; after the MFMAs of step kk the K reads of step
+//   kk + kKAhead, or, once those are exhausted, the reads of two V fragments; the PV product
+//   starts by requesting the rest of the first kVAhead V fragments and then, after the MFMA
+//   of fragment c = 4*st + db, requests fragment c + kVAhead.
+constexpr int kKAhead = 3;     // contraction steps of K fragments in flight (2 fragments each)
+constexpr int kVAhead = 6;     // V fragments in flight (2 transposing reads each)
+constexpr int kVEarly = 2 * kKAhead;   // V fragments requested during the score MFMAs
+
+// LDS reads issued before the score MFMAs of step kk wait for their fragments
+constexpr int issued_at_qk(int kk, bool with_v) {
+  const int k_reads = 2 * (kk + kKAhead < 8 ? kk + kKAhead : 8);
+  const int v_frags = with_v && kk + kKAhead > 8 ? 2 * (kk + kKAhead - 8) : 0;
+  return k_reads + 2 * v_frags;
+}
+
+template <int kVOff, int c>
+__device__ __forceinline__ void issue_v_fragment(const OperandAddr& oa, u32x2 (&vf)[16][2]) {
+  lds_issue_tr64_x<kVOff + (c / 4) * kVStepBytes, 0>(vf[c][0], oa.v[c % 4]);
+  lds_issue_tr64_x<kVOff + (c / 4) * kVStepBytes + 8 * kRowElems * 2, 16>(vf[c][1], oa.v[c % 4]);
+}
+
+// S^T = K Q^T for the K tile at byte offset kKOff from the addresses in `oa`.  kWithV: also
+// start the V^T reads of fragments 0..kVEarly-1 of the V tile at byte offset kVOff.
+// `pre()` runs once the first K reads are out and before the first MFMA waits for them;
+// `mid(kk)` after the MFMAs of contraction step kk have been handed over: work that only issues
+// (LDS reads of its own, tile fetches for the next step) goes there, under the matrix pipe's
+// shadow.  LDS reads issued from the hooks make the fragment waits a little conservative
+// (they count only the fragment reads), never wrong.
+template <int kKOff, int kVOff, bool kWithV, class Pre, class Mid>
+__device__ __forceinline__ void qk_tile_sched(const OperandAddr& oa, const bf16x8 (&qf)[8], f32x16 (&s)[2],
+                                              u32x2 (&vf)[16][2], Pre&& pre, Mid&& mid) {
+  bf16x8 ka[8][2];
+  static_for<0, kKAhead>([&](auto kk_) {
+    constexpr int kk = decltype(kk_)::value;
+    lds_issue_b128_x2<kKOff, (kk << 5)>(ka[kk][0], ka[kk][1], oa.k0);
+  });
+  pre();
+  static_for<0, 8>([&](auto kk_) {
+    constexpr int kk = decltype(kk_)::value;
+    lds_wait<issued_at_qk(kk, kWithV) - (2 * kk + 2)>(ka[kk][0], ka[kk][1]);
+    if constexpr (kk == 0) {
+      f32x16 z;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) z[i] = 0.f;
+      s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk][0], qf[kk], z, 0, 0, 0);
+      s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk][1], qf[kk], z, 0, 0, 0);
+    } else {
+      s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk][0], qf[kk], s[0], 0, 0, 0);
+      s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk][1], qf[kk], s[1], 0, 0, 0);
+    }
+    if constexpr (kk + kKAhead < 8) {
+      lds_issue_b128_x2<kKOff, ((kk + kKAhead) << 5)>(ka[kk + kKAhead][0], ka[kk + kKAhead][1], oa.k0);
+    } else if constexpr (kWithV) {
+      issue_v_fragment<kVOff, 2 * (kk + kKAhead - 8)>(oa, vf);
+      issue_v_fragment<kVOff, 2 * (kk + kKAhead - 8) + 1>(oa, vf);
+    }
+    mid(kk_);
+  });
+}
+template <int kKOff, int kVOff, bool kWithV>
+__device__ __forceinline__ void qk_tile_sched(const OperandAddr& oa, const bf16x8 (&qf)[8], f32x16 (&s)[2],
+                                              u32x2 (&vf)[16][2]) {
+  qk_tile_sched<kKOff, kVOff, kWithV>(oa, qf, s, vf, [] {}, [](auto) {});
+}
+
+// The V^T reads qk_tile_sched started are not going to be used: their target registers stay
+// claimed until the data has arrived (an LDS read that lands later would overwrite whatever
+// the registers had been given to).
+__device__ __forceinline__ void abandon_v_fragments(u32x2 (&vf)[16][2]) {
+  static_for<0, kVEarly>([&](auto c_) { lds_wait<0>(vf[decltype(c_)::value][0], vf[decltype(c_)::value][1]); });
+}
+
+// O^T += V^T P^T.  kEarly: fragments 0..kVEarly-1 were requested by qk_tile_sched.
+template <int kVOff, bool kEarly>
+__device__ __forceinline__ void pv_tile_sched(const OperandAddr& oa, const bf16x8 (&pb)[4], f32x16 (&o)[4],
+                                              u32x2 (&vf)[16][2]) {
+  static_for<(kEarly ? kVEarly : 0), kVAhead>([&](auto c_) { issue_v_fragment<kVOff, decltype(c_)::value>(oa, vf); });
+  static_for<0, 16>([&](auto c_) {
+    constexpr int c = decltype(c_)::value, st = c / 4, db = c % 4;
+    // V reads issued so far: fragments 0..kVAhead-1 and fragment c' + kVAhead after every earlier c'
+    constexpr int frags = (c + kVAhead < 16 ? c + kVAhead : 16);
+    lds_wait<2 * frags - (2 * c + 2)>(vf[c][0], vf[c][1]);
+    const u32x4 w = {vf[c][0].x, vf[c][0].y, vf[c][1].x, vf[c][1].y};
+    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), pb[st], o[db], 0, 0, 0);
+    if constexpr (c + kVAhead < 16) issue_v_fragment<kVOff, c + kVAhead>(oa, vf);
+  });
+}
+
+// The same two products for a step that does them back to back (PV right after its scores).
+template <int kKOff, class Pre, class Mid>
+__device__ __forceinline__ void qk_tile_only(const OperandAddr& oa, const bf16x8 (&qf)[8], f32x16 (&s)[2], Pre&& pre,
+                                             Mid&& mid) {
+  u32x2 none[16][2];
+  qk_tile_sched<kKOff, 0, false>(oa, qf, s, none, pre, mid);
+}
+template <int kKOff>
+__device__ __forceinline__ void qk_tile_only(const OperandAddr& oa, const bf16x8 (&qf)[8], f32x16 (&s)[2]) {
+  qk_tile_only<kKOff>(oa, qf, s, [] {}, [](auto) {});
+}
+template <int kVOff>
+__device__ __forceinline__ void pv_tile_only(const OperandAddr& oa, const bf16x8 (&pb)[4], f32x16 (&o)[4]) {
+  u32x2 vf[16][2];
+  pv_tile_sched<kVOff, false>(oa, pb, o, vf);
+}
+
+// Value of the lane 32 away, combined with the lane's own (the two halves of a query row's
+// statistics): v_permlane32_swap exchanges the upper half of one register with the lower half
+// of another, so two copies of x come back as (x of lanes 0..31, x of lanes 32..63) in every
+// lane -- no LDS round trip as with a bpermute.
+__device__ __forceinline__ float xhalf_max(float x) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
+__device__ __forceinline__ float xhalf_sum(float x) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r.x) + __uint_as_float(r.y);
+}
+
 // What a tile's score step hands to its PV step and to the row statistics.
 struct TileStats {
   float alpha;   // factor that moves the old terms to the reference used for this tile (1 if unchanged)
@@ -185,7 +409,7 @@ __device__ __forceinline__ TileStats softmax_tile(f32x16 (&s)[2], float c2, floa
       }
       mx = fmaxf(mx, s[nb][i]);
     }
-  mx = fmaxf(mx, __shfl_xor(mx, 32)) * c2;
+  mx = xhalf_max(mx) * c2;
   TileStats t;
   t.grow = mx > m_ref + kLazy;
   t.m_use = t.grow ? mx : m_ref;
@@ -199,7 +423,7 @@ __device__ __forceinline__ TileStats softmax_tile(f32x16 (&s)[2], float c2, floa
       s[nb][i] = pe;
       sum += pe;
     }
-  sum += __shfl_xor(sum, 32);
+  sum = xhalf_sum(sum);
   t.mass = sum;
   t.alpha = t.grow ? __builtin_amdgcn_exp2f(m_ref - t.m_use) : 1.0f;
   t.prev = l_run * t.alpha;

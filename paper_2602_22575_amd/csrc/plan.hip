@@ -141,9 +141,17 @@ size_t plan_scratch_bytes(int Z, int H, int Hkv, int L, int S, int non_causal) {
 }
 
 // ---------------------------------------------------------------------------------------
-__global__ void init_kernel(Scratch s, int64_t rows) {
+__global__ void init_kernel(Scratch s, int64_t rows, int32_t* status) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < 16) s.counters[i] = 0;
+  if (i == 0 && status) *status = 0;
+}
+
+// A broken invariant (see the S2O_PLAN_* bits) is recorded in the scratch counters and, if the
+// caller gave one, in the status word; nothing is ever dropped silently.
+__device__ inline void raise(const PlanArgs& a, const Scratch& sc, uint32_t bit) {
+  atomicOr(&sc.counters[2], bit);
+  if (a.status) atomicOr(reinterpret_cast<unsigned int*>(a.status), bit);
 }
 
 // k_guide[z,g,:] = mean_{s<S} K[z,g,s,:]
@@ -520,7 +528,7 @@ __global__ __launch_bounds__(256) void scatter_kernel(PlanArgs a, Scratch sc) {
         stage[slot] = sort_key(sv, (uint32_t)(t0 + e));
         sdst[slot] = delta[bk] + slot;
       } else {
-        sc.counters[2] = 1u;
+        raise(a, sc, 1u);
       }
     }
   }
@@ -529,7 +537,7 @@ __global__ __launch_bounds__(256) void scatter_kernel(PlanArgs a, Scratch sc) {
   for (int i = tid; i < n_here; i += 256) {
     const uint32_t d = sdst[i];
     if (d < (uint32_t)lim) sc.pairs[base + d] = stage[i];
-    else sc.counters[2] = 1u;
+    else raise(a, sc, 8u);
   }
 }
 
@@ -602,17 +610,23 @@ __global__ __launch_bounds__(4 * kNBMax) void scan_kernel(PlanArgs a, Scratch sc
       off += cnt;
     }
     if (off > span_begin) lspan[ns++] = make_int2((int)span_begin, (int)off);
-    if (off != (uint32_t)len) sc.counters[2] = 2u;
+    if (off != (uint32_t)len) raise(a, sc, 2u);
     nsp[0] = ns; nsp[1] = nbig;
     // one reservation per list instead of one (slow, serialised) atomic per span
     gbase[0] = ns ? atomicAdd(&sc.counters[0], ns) : 0u;
     gbase[1] = nbig ? atomicAdd(&sc.counters[1], nbig) : 0u;
   }
   __syncthreads();
-  if (threadIdx.x < nsp[0] && (int64_t)(gbase[0] + threadIdx.x) < sc.max_spans)
-    sc.spans[gbase[0] + threadIdx.x] = make_int4((int)row_id, lspan[threadIdx.x].x, lspan[threadIdx.x].y, 0);
-  if (threadIdx.x < nsp[1] && (int64_t)(gbase[1] + threadIdx.x) < sc.max_spans)
-    sc.bigspans[gbase[1] + threadIdx.x] = make_int4((int)row_id, lbig[threadIdx.x].x, lbig[threadIdx.x].y, 0);
+  if (threadIdx.x < nsp[0]) {
+    if ((int64_t)(gbase[0] + threadIdx.x) < sc.max_spans)
+      sc.spans[gbase[0] + threadIdx.x] = make_int4((int)row_id, lspan[threadIdx.x].x, lspan[threadIdx.x].y, 0);
+    else raise(a, sc, 4u);
+  }
+  if (threadIdx.x < nsp[1]) {
+    if ((int64_t)(gbase[1] + threadIdx.x) < sc.max_spans)
+      sc.bigspans[gbase[1] + threadIdx.x] = make_int4((int)row_id, lbig[threadIdx.x].x, lbig[threadIdx.x].y, 0);
+    else raise(a, sc, 4u);
+  }
   __syncthreads();
   if (b < nb) {
     uint32_t running = bstart[b];
@@ -829,7 +843,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
     if (se != hipSuccess) return se;
   }
 
-  hipLaunchKernelGGL(init_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream, sc, rows);
+  hipLaunchKernelGGL(init_kernel, dim3(1), dim3(64), 0, stream, sc, rows, a.status);
   hipLaunchKernelGGL(kguide_kernel, dim3(a.Z * a.Hkv * kGuideParts), dim3(256), 0, stream, a, sc);
   {
     int n2 = 1;
@@ -846,7 +860,7 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
     {
       int ns2 = 1;
       while (ns2 < a.L / kSampleStride) ns2 <<= 1;
-      if ((size_t)ns2 * 8 > kSplitterLdsMax) return hipErrorInvalidValue;   // L > 1M tokens
+      if ((size_t)ns2 * 8 > kSplitterLdsMax) return hipErrorInvalidValue;   // unreachable: the API refuses L > 1M tokens
       hipLaunchKernelGGL(splitter_kernel, dim3((unsigned)rows), dim3(256), (size_t)ns2 * 8, stream, a, sc);
     }
     const dim3 cgrid((unsigned)(rows * sc.maxch));

@@ -5,17 +5,19 @@
 // One workgroup = 4 wavefronts = 128 permuted query rows of one (batch, head, segment): two
 // query tiles of 64 rows or one of 128, 32 rows per wavefront.  The wavefronts of a segment
 // walk the same KV_perm row, so a gathered 64-token K/V tile is staged in LDS once per
-// workgroup.  MFMA formulation, LDS layouts and the base-2 online softmax with lazy rescaling
-// are in attn_tile.h; the early-stop vote is taken one tile late, the PV product of a tile
-// waiting for it.
+// workgroup.  MFMA formulation, LDS layouts, the explicitly scheduled operand reads and the
+// base-2 online softmax with lazy rescaling are in attn_tile.h; the early-stop vote is taken
+// one tile late, the PV product of a tile waiting for it.
 //
-// What differs is the tile pipeline.  Because the PV product of tile k runs during step k+1,
-// V tile k is only needed one step after K tile k, so it is also fetched one step later:
-// step k reads K(k) and V(k-1) while K(k+1) and V(k) arrive.  Two K and two V buffers
-// (64 KB) then suffice where fetching K and V together needs a third V buffer, and with
-// 4 wavefronts of under 256 registers two workgroups share a CU: their barriers are
-// independent and one's prologue (Q gather, 2 KB of state per row), stop/drain tail and
-// epilogue overlap the other's tiles.
+// Tile pipeline.  Because the PV product of tile k runs during step k+1, V tile k is only
+// needed one step after K tile k, so it is also fetched one step later: step k reads K(k) and
+// V(k-1) while K(k+1) and V(k) arrive.  Two K and two V buffers (64 KB) then suffice, and with
+// 4 wavefronts of under 256 registers two workgroups share a CU.
+// A step is:   read the votes on tile k-1  ->  issue the fetches of K(k+1), V(k) and of the
+// token indices of tile k+2  ->  scores of tile k, PV of tile k-1, softmax of tile k  ->  wait
+// for the wavefront's own fetches  ->  barrier.  The fetches are issued first and waited for
+// last, so they have the whole step to land; nothing between depends on them (the indices
+// loaded in step k are first touched at the top of step k+1).
 #include "attn_tile.h"
 #include "s2o_internal.h"
 
@@ -26,18 +28,23 @@ namespace {
 using namespace tile;
 
 constexpr int kWaves = 4, kThreads = 64 * kWaves;
-constexpr size_t kPrefixLds = (size_t)(4 * kTileElems) * 2 + 64;   // K x2, V x2, vote flags
+constexpr int kKBytes0 = 0, kVBytes0 = 2 * kTileBytes;             // K x2 at 0, V x2 behind them
+constexpr size_t kPrefixLds = (size_t)(4 * kTileBytes) + 64 + 4 * kWaves * 64;   // + vote flags + index ring
+
+template <int P> using Par = std::integral_constant<int, P>;
 
 // kNoStop: stop_mode 2 (every prefix tile folded in, the paper's kernel C) as an instantiation
 // of its own, so that neither loop's registers weigh on the other.
 template <bool kNoStop>
 __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs a) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  extern __shared__ __attribute__((aligned(256))) unsigned char smem[];   // OperandAddr needs a 256-byte base
   uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
   uint16_t* Vt = Ks + 2 * kTileElems;
   int* sflag = reinterpret_cast<int*>(Vt + 2 * kTileElems);   // stop votes: two sets of kWaves
+  int32_t* ring = reinterpret_cast<int32_t*>(smem + 4 * kTileBytes + 64);   // map entries: 4 tiles x kWaves x 16
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int m_ = lane & 31, hh = lane >> 5;
   const int G = a.H / a.Hkv;
   const int BM = a.BM;                                   // query tile rows: 64 or 128
@@ -70,57 +77,72 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   const bool active = j < TJ;
 
   // ---- loader: every wavefront moves 16 rows of K and 16 rows of V per step, 4 rows per
-  // instruction.  The token indices are read two tiles ahead of the K fetch that uses them,
-  // so a fetch never waits for its own index loads; the V fetch of a tile reuses its K
-  // fetch's indices.
+  // instruction (lane l of group gi moves a chunk of tile row 16*wave + 4*gi + l/16).  The map
+  // entries of its rows travel through a small ring in LDS, private to the wavefront: the 16
+  // entries of tile t+2 are requested (global -> LDS, like the tiles) at the top of step t and
+  // first read at the top of step t+1, so no register holds an index across a step and no
+  // fetch ever waits for an index load.  Ring position 4*(l/16) + gi holds the entry of row
+  // 4*gi + l/16, so a lane gets its four tokens with one 16-byte read.
   const uint32_t k_stride_bytes = (uint32_t)(a.ks[2] * 2), v_stride_bytes = (uint32_t)(a.vs[2] * 2);
-  int goff[4];
+  uint32_t goff[4];
 #pragma unroll
-  for (int gi = 0; gi < 4; ++gi) goff[gi] = load_chunk_offset(lane, 16 * wave + 4 * gi);
-  uint32_t tokk[4], tokv[4];            // tokens of the next K tile and of the next V tile
-  auto load_index = [&](int t) {        // tokk <- tile t (clamped); only called when ntiles > 0
-    const int pt = min(t, ntiles - 1);
-    if (a.kv_perm) {
-#pragma unroll
-      for (int gi = 0; gi < 4; ++gi) {
-        const int tk = kvrow[(int64_t)pt * kBN + 16 * wave + 4 * gi + (lane >> 4)];
-        tokk[gi] = (uint32_t)min(max(tk, 0), a.L - 1);
-      }
-    } else {                            // no map (non-causal only): the keys in storage order
-#pragma unroll
-      for (int gi = 0; gi < 4; ++gi) tokk[gi] = (uint32_t)(pt * kBN + 16 * wave + 4 * gi + (lane >> 4));
+  for (int gi = 0; gi < 4; ++gi) goff[gi] = (uint32_t)load_chunk_offset(lane, 16 * wave + 4 * gi);
+  auto ring_slot = [&](int t) { return ring + (t & 3) * (16 * kWaves) + 16 * wave; };
+  const int ring_row = 16 * wave + 4 * (lane & 3) + ((lane >> 2) & 3);     // row whose entry lane l < 16 requests
+  auto fetch_index = [&](int t) {       // map entries of tile t (clamped tile number) -> ring; ntiles > 0
+    if (a.kv_perm && lane < 16) {
+      const int32_t* tile_idx = kvrow + (int64_t)min(t, ntiles - 1) * kBN;
+      __builtin_amdgcn_global_load_lds((const gvoid*)(tile_idx + ring_row), (lvoid*)ring_slot(t), 4, 0, 0);
     }
   };
-  auto load_k = [&](int t) {            // K tile t (its tokens are in tokk) -> buffer t & 1
+  auto tokens = [&](int t, uint32_t (&tok)[4]) {   // this lane's four tokens of tile t, clamped to the sequence
+    if (a.kv_perm) {
+      const int4 e = *reinterpret_cast<const int4*>(ring_slot(t) + 4 * (lane >> 4));
+      const int ev[4] = {e.x, e.y, e.z, e.w};
+#pragma unroll
+      for (int gi = 0; gi < 4; ++gi) tok[gi] = (uint32_t)min(max(ev[gi], 0), a.L - 1);
+    } else {                            // no map (non-causal only): the keys in storage order
+#pragma unroll
+      for (int gi = 0; gi < 4; ++gi)
+        tok[gi] = (uint32_t)min(min(t, ntiles - 1) * kBN + 16 * wave + 4 * gi + (lane >> 4), a.L - 1);
+    }
+  };
+  auto load_k = [&](int t, const uint32_t (&tok)[4]) {   // K tile t -> buffer t & 1
     uint16_t* kd = Ks + (t & 1) * kTileElems;
 #pragma unroll
     for (int gi = 0; gi < 4; ++gi)
-      load_rows_to_lds(reinterpret_cast<const char*>(Kh) + (uint64_t)tokk[gi] * k_stride_bytes + goff[gi],
+      load_rows_to_lds(reinterpret_cast<const char*>(Kh) + (uint64_t)(__umul24(tok[gi], k_stride_bytes) + goff[gi]),
                        kd + (16 * wave + 4 * gi) * kRowElems);
   };
-  auto load_v = [&](int t) {            // V tile t (its tokens are in tokv) -> buffer t & 1
+  auto load_v = [&](int t, const uint32_t (&tok)[4]) {   // V tile t -> buffer t & 1
     uint16_t* vd = Vt + (t & 1) * kTileElems;
 #pragma unroll
     for (int gi = 0; gi < 4; ++gi)
-      load_rows_to_lds(reinterpret_cast<const char*>(Vh) + (uint64_t)tokv[gi] * v_stride_bytes + goff[gi],
+      load_rows_to_lds(reinterpret_cast<const char*>(Vh) + (uint64_t)(__umul24(tok[gi], v_stride_bytes) + goff[gi]),
                        vd + (16 * wave + 4 * gi) * kRowElems);
   };
-  // the fetches of step t: K(t+1) and V(t); afterwards tokk holds tile t+2, tokv tile t+1
-  auto load_step = [&](int t) {
-    if (t + 1 < ntiles) load_k(t + 1);
-    load_v(t);
-#pragma unroll
-    for (int gi = 0; gi < 4; ++gi) tokv[gi] = tokk[gi];
-    load_index(t + 2);
+  // the fetches of step t (top of the step): K(t+1), V(t) (no stop rule: V(t+1)), indices of tile t+2
+  auto fetch_step = [&](int t) {
+    uint32_t tn[4];
+    tokens(t + 1, tn);
+    if (kNoStop) {
+      if (t + 1 < ntiles) { load_k(t + 1, tn); load_v(t + 1, tn); }
+    } else {
+      uint32_t tc[4];
+      tokens(t, tc);
+      if (t + 1 < ntiles) load_k(t + 1, tn);
+      load_v(t, tc);
+    }
+    fetch_index(t + 2);
   };
-  constexpr bool no_stop = kNoStop;        // no stop rule: PV follows its scores at once, V comes with K
   if (ntiles > 0) {
-    load_index(0);
-    load_k(0);
-#pragma unroll
-    for (int gi = 0; gi < 4; ++gi) tokv[gi] = tokk[gi];
-    if (no_stop) load_v(0);
-    load_index(1);
+    fetch_index(0);
+    fetch_index(1);
+    wait_tile_loads();
+    uint32_t t0[4];
+    tokens(0, t0);
+    load_k(0, t0);
+    if (kNoStop) load_v(0, t0);
   }
 
   // ---- the query row of this lane and its Q fragments
@@ -132,8 +154,8 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
     qoff = min(max(qoff, 0), a.S - 1);
     load_q(Qh + (int64_t)(nS + qoff) * a.qs[2], hh, qf);
   }
-  Operands op;
-  op.init(lane);
+  OperandAddr oa;
+  oa.init(lane, lds_address(smem));
 
   // ---- online-softmax state and output accumulator O^T[d-block], resumed from the state
   // buffers (row (z, h, l) -> accumulator, l, m).  The statistics are needed by the first
@@ -154,9 +176,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
 
   f32x16 s[2];
   TileStats ts;
-  auto qk = [&](int kbuf) { qk_tile(Ks + kbuf * kTileElems, op, qf, s); };
   auto softmax = [&] { ts = softmax_tile<false>(s, c2, m_ref, l_run, 0, 0, hh); };
-  auto pv = [&](int vbuf, const bf16x8 (&pb)[4]) { pv_tile(Vt + vbuf * kTileElems, op, pb, o); };
 
   // ---- prefix tiles in KV_perm order with the early-stop rule: the query tile continues iff
   // some row's tile mass reaches tau * (mass so far).  The wavefronts of a tile vote through
@@ -190,47 +210,53 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
     for (int w = 0; w < kWaves; ++w) any |= vf[w];
     return any;
   };
+  auto end_step = [&] {                 // this wavefront's fetches have landed; everyone's after the barrier
+    wait_tile_loads();
+    __syncthreads();
+  };
 
   bool acc_loaded = false;
-  if (no_stop && ntiles > 0) {
+  if (kNoStop && ntiles > 0) {
     // ---- every prefix tile is folded in (no votes, nothing deferred): step k reads K(k) and
     // V(k) while K(k+1) and V(k+1) arrive
-    __syncthreads();                            // K and V tile 0 have landed
-    for (int it = 0; it < ntiles; ++it) {
-      if (it + 1 < ntiles) {
-        load_k(it + 1);
-#pragma unroll
-        for (int gi = 0; gi < 4; ++gi) tokv[gi] = tokk[gi];
-        load_v(it + 1);
-        load_index(it + 2);
-      }
+    end_step();                                   // K and V tile 0 have landed
+    auto plain_step = [&](auto par_, int it) {
+      constexpr int P = decltype(par_)::value;
+      fetch_step(it);
       if (active) {
-        qk(it & 1);
+        qk_tile_only<kKBytes0 + P * kTileBytes>(oa, qf, s);
         if (!acc_loaded) { init_acc(); acc_loaded = true; }
         softmax();
         pack_p(s, pb_pend);
         rescale(o, ts.alpha, ts.grow);
-        pv(it & 1, pb_pend);
+        pv_tile_only<kVBytes0 + P * kTileBytes>(oa, pb_pend, o);
         l_run = ts.prev + ts.mass; m_ref = ts.m_use;
         ++committed; ++issued;
       }
-      __syncthreads();
+      end_step();
+    };
+    for (int it = 0; it < ntiles; it += 2) {
+      plain_step(Par<0>{}, it);
+      if (it + 1 < ntiles) plain_step(Par<1>{}, it + 1);
     }
   } else if (ntiles > 0) {
-    __syncthreads();                            // K tile 0 has landed
+    end_step();                                   // K tile 0 has landed
     int it = 0;
     bool wg_done = false;
     if (active) {
       // first tile: scores only
-      load_step(0);
-      qk(0);
+      fetch_step(0);
+      qk_tile_only<kKBytes0>(oa, qf, s);
       init_acc(); acc_loaded = true;
       softmax();
       publish(0);
-      __syncthreads();
+      end_step();
       bool pending = true;                      // a scored tile waits for its vote
-      for (it = 1; it < ntiles; ++it) {
-        const int* vf = vote_flags(it - 1);
+      // one step; tile `it` has parity P: K(it) sits in K buffer P, V(it-1) in V buffer 1-P.
+      // Returns false when the query tile stops at this step.
+      auto step = [&](auto par_, int it_) -> bool {
+        constexpr int P = decltype(par_)::value;
+        const int* vf = vote_flags(it_ - 1);
         const int votes = tile_votes(vf);
         if (votes == 0) {
           const int any = wg_votes(vf);
@@ -238,21 +264,31 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
             l_run = l_save; m_ref = m_save;
           } else {
             rescale(o, alpha_pend, grow_pend);
-            pv((it - 1) & 1, pb_pend);
+            pv_tile_only<kVBytes0 + (1 - P) * kTileBytes>(oa, pb_pend, o);
             ++committed;
           }
           pending = false;
           wg_done = any == 0;
-          break;
+          return false;
         }
-        qk(it & 1);
-        load_step(it);
+        fetch_step(it_);
+        u32x2 vfr[16][2];
+        qk_tile_sched<kKBytes0 + P * kTileBytes, kVBytes0 + (1 - P) * kTileBytes, true>(oa, qf, s, vfr);
         rescale(o, alpha_pend, grow_pend);
-        pv((it - 1) & 1, pb_pend);
+        pv_tile_sched<kVBytes0 + (1 - P) * kTileBytes, true>(oa, pb_pend, o, vfr);
         ++committed;
         softmax();
-        publish(it);
+        publish(it_);
+        wait_tile_loads();
         __syncthreads();
+        return true;
+      };
+      for (it = 1; it < ntiles;) {
+        if (!step(Par<1>{}, it)) break;
+        ++it;
+        if (it >= ntiles) break;
+        if (!step(Par<0>{}, it)) break;
+        ++it;
       }
       if (pending) {                            // the last tile: its vote is visible now
         const bool stop = tile_votes(vote_flags(ntiles - 1)) == 0;
@@ -260,7 +296,8 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
           l_run = l_save; m_ref = m_save;
         } else {
           rescale(o, alpha_pend, grow_pend);
-          pv((ntiles - 1) & 1, pb_pend);
+          if ((ntiles - 1) & 1) pv_tile_only<kVBytes0 + kTileBytes>(oa, pb_pend, o);
+          else pv_tile_only<kVBytes0>(oa, pb_pend, o);
           ++committed;
         }
         wg_done = true;
@@ -270,9 +307,9 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
     if (!wg_done) {
       for (; it < ntiles; ++it) {
         if (it > 0 && wg_votes(vote_flags(it - 1)) == 0) break;
-        load_step(it);
+        fetch_step(it);
         if (lane == 0) vote_flags(it)[wave] = 0;
-        __syncthreads();
+        end_step();
       }
     }
   }

@@ -70,6 +70,7 @@ struct PlanArgs {
   float* s_k;
   float* q_mean;
   float* k_guide;
+  int32_t* status;   // optional: receives the S2O_PLAN_* bits (0 = every invariant held)
   int Z, H, Hkv, L, S, N;
   int non_causal;
   int64_t qs[3], ks[3];

@@ -23,6 +23,7 @@ def gpu_plan(w, Qd, Kd, non_causal=0):
     p = params_for(w, non_causal=non_causal)
     out = s2o.s2o_plan(Qd, Kd, p, want_scores=True)
     torch.cuda.synchronize()
+    assert int(out.status.item()) == 0, f"plan status {int(out.status.item())} (S2O_PLAN_* bits)"
     return out, {k: getattr(out, k).cpu().numpy() for k in ("q_perm", "kv_perm", "s_q", "s_k", "q_mean", "k_guide")}
 
 

@@ -23,12 +23,12 @@ def test_every_declared_symbol_is_exported(lib):
     assert declared == set(b.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.s2o_version() == 3
+    assert lib.s2o_version() == 4
 
 
 def test_struct_layout_matches_header(lib):
     assert C.sizeof(b.S2OParams) == 14 * 4 + 12 * 8
-    assert C.sizeof(b.S2OPlanOut) == 6 * 8
+    assert C.sizeof(b.S2OPlanOut) == 7 * 8
 
 
 def test_size_queries():
@@ -67,6 +67,9 @@ def test_size_queries():
     (dict(use_q_perm=5), b.S2O_EINVAL),
     (dict(softmax_scale=-1.0), b.S2O_EINVAL),
     (dict(q_stride=(0, 0, 100)), b.S2O_EINVAL),   # row stride not 16-byte aligned / < D
+    (dict(L=2 << 20, S=2048), b.S2O_EUNSUPPORTED),          # plan: a row's sample no longer fits the LDS sort
+    (dict(k_stride=(1 << 40, 1 << 36, 1 << 23)), b.S2O_EUNSUPPORTED),   # a K row stride of 16 MiB
+    (dict(L=1 << 20, S=2048, v_stride=(1 << 40, 1 << 36, 4096)), b.S2O_EUNSUPPORTED),   # a V head beyond 4 GiB
 ])
 def test_bad_params_are_rejected(kw, code):
     base = dict(Z=1, H=4, Hkv=2, L=1024, D=128, S=256)
@@ -74,6 +77,16 @@ def test_bad_params_are_rejected(kw, code):
     with pytest.raises(b.S2OError) as e:
         b.s2o_plan_sizes(b.make_params(**base))
     assert e.value.code == code
+
+
+def test_plan_status_bits_are_declared():
+    """The status word of s2o_plan_out and its bits exist in the header and in the binding."""
+    header = open(os.path.join(ROOT, "include", "s2o.h")).read()
+    for name, bit in (("S2O_PLAN_STAGE_OVERFLOW", 1), ("S2O_PLAN_COUNT_MISMATCH", 2), ("S2O_PLAN_SPAN_OVERFLOW", 4),
+                      ("S2O_PLAN_BAD_RANK", 8)):
+        assert re.search(rf"{name}\s*=\s*{bit}\b", header), name
+    assert re.search(r"int32_t\*\s*status;", header)
+    assert [f[0] for f in b.S2OPlanOut._fields_][-1] == "status"
 
 
 def test_segment_length_limit_applies_to_the_plan_only():
