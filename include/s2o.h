@@ -127,6 +127,23 @@ int s2o_plan_sizes(const s2o_params* params, size_t* q_perm_bytes, size_t* kv_pe
 int s2o_plan(const void* Q, const void* K, const s2o_params* params, const s2o_plan_out* out,
              void* scratch, size_t scratch_bytes, void* stream);
 
+/* s2o_plan for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same ranking, with the scratch taken
+ * from an array built into the library instead of a caller buffer.  The call allocates and
+ * frees nothing (the array's address is looked up once per GPU, on the first call there).
+ *   - Limit: configurations whose s2o_plan_sizes scratch_bytes exceed S2O_STATIC_SCRATCH_BYTES
+ *     are refused with S2O_ESCRATCH before anything is enqueued (e.g. the Llama-3.1-8B head
+ *     shape fits up to 8K tokens at S = 1024; 128K needs s2o_plan with a caller buffer).
+ *   - Every GPU the library is loaded on holds the array until the process ends.
+ *   - All calls on one GPU share that GPU's array: calls whose kernels may overlap (different
+ *     streams, or other host threads) race; order them.  Contents do not survive the call; what
+ *     the kernels need at zero is cleared by the call itself (by a kernel, so the call can be
+ *     captured like s2o_plan).
+ * Outputs and return codes as for s2o_plan. */
+#define S2O_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int s2o_plan_static(const void* Q, const void* K, const s2o_params* params, const s2o_plan_out* out,
+                    void* stream);
+
 /* Byte sizes of one counts array ([Z,H,L/B_M] int32) and of the optional attention scratch
  * (the per-row state buffers of the two-pass form, fp32 [Z,H,L,D+2]; 0 when non_causal). */
 int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* scratch_bytes);

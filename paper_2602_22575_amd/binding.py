@@ -15,7 +15,9 @@ LIB_PATH = os.path.join(_HERE, "libs2o.so")
 
 S2O_OK, S2O_EINVAL, S2O_EUNSUPPORTED, S2O_ESCRATCH, S2O_EHIP = 0, -1, -2, -3, -4
 
-EXPORTS = ("s2o_version", "s2o_strerror", "s2o_last_hip_error", "s2o_plan_sizes", "s2o_plan",
+STATIC_SCRATCH_BYTES = 32 << 20
+
+EXPORTS = ("s2o_version", "s2o_strerror", "s2o_last_hip_error", "s2o_plan_sizes", "s2o_plan", "s2o_plan_static",
            "s2o_attention_sizes", "s2o_attention", "s2o_attention_local", "s2o_attention_prefix")
 
 
@@ -64,6 +66,8 @@ def load_library():
     lib.s2o_plan.restype = C.c_int
     lib.s2o_plan.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(S2OParams), C.POINTER(S2OPlanOut),
                              C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.s2o_plan_static.restype = C.c_int
+    lib.s2o_plan_static.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(S2OParams), C.POINTER(S2OPlanOut), C.c_void_p]
     lib.s2o_attention_sizes.restype = C.c_int
     lib.s2o_attention_sizes.argtypes = [C.POINTER(S2OParams), szp, szp]
     lib.s2o_attention.restype = C.c_int
@@ -172,11 +176,12 @@ class Plan:
 
 
 def s2o_plan(Q, K, params: S2OParams, want_scores: bool = True, scratch=None, stream=None,
-             maps=None) -> Plan:
+             maps=None, static_scratch: bool = False) -> Plan:
     """Step 1.  Q, K: torch CUDA bf16 tensors [Z,H,L,D] / [Z,Hkv,L,D].  Returns device
     tensors; the call is asynchronous on the current (or given) torch stream.
     maps: optional (q_perm [Z,H,N,S], kv_perm [Z,H,max(P,4)]) int32 tensors to write into
-    (P = entries of the key rows of one head: S*N(N-1)/2, or N*L when params.non_causal)."""
+    (P = entries of the key rows of one head: S*N(N-1)/2, or N*L when params.non_causal).
+    static_scratch: call s2o_plan_static (the library's built-in scratch) instead of s2o_plan."""
     import torch
     lib = load_library()
     _check_qkv(params, Q=Q, K=K)
@@ -199,7 +204,7 @@ def s2o_plan(Q, K, params: S2OParams, want_scores: bool = True, scratch=None, st
         out.s_k = torch.empty((Z, H, max(P, 4)), dtype=torch.float32, device=dev)
         out.q_mean = torch.empty((Z, H, N, D), dtype=torch.float32, device=dev)
         out.k_guide = torch.empty((Z, Hkv, D), dtype=torch.float32, device=dev)
-    own_scratch = scratch is None
+    own_scratch = scratch is None and not static_scratch
     if own_scratch:
         scratch = torch.empty(sz["scratch"], dtype=torch.uint8, device=dev)
     out.status = torch.empty(1, dtype=torch.int32, device=dev)
@@ -207,8 +212,11 @@ def s2o_plan(Q, K, params: S2OParams, want_scores: bool = True, scratch=None, st
                    None if maps is not None else out.q_perm, None if maps is not None else out.kv_perm)
     po = S2OPlanOut(_ptr(out.q_perm), _ptr(out.kv_perm), _ptr(out.s_q), _ptr(out.s_k),
                     _ptr(out.q_mean), _ptr(out.k_guide), _ptr(out.status))
-    _check(lib.s2o_plan(Q.data_ptr(), K.data_ptr(), C.byref(params), C.byref(po),
-                        scratch.data_ptr(), scratch.numel(), _stream_handle(stream)))
+    if static_scratch:
+        _check(lib.s2o_plan_static(Q.data_ptr(), K.data_ptr(), C.byref(params), C.byref(po), _stream_handle(stream)))
+    else:
+        _check(lib.s2o_plan(Q.data_ptr(), K.data_ptr(), C.byref(params), C.byref(po),
+                            scratch.data_ptr(), scratch.numel(), _stream_handle(stream)))
     if P == 0:
         out.kv_perm = out.kv_perm[:, :, :0]
         if out.s_k is not None:

@@ -70,8 +70,10 @@ int check_params(const s2o_params* p, Shape* s, bool for_plan = false) {
 
 bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 
+// s2o_plan and s2o_plan_static: the same validation and launches; the second takes the
+// library's built-in scratch array (looked up per device, nothing allocated).
 int plan_call(const void* Q, const void* K, const s2o_params* params, const s2o_plan_out* out, void* scratch,
-              size_t scratch_bytes, void* stream) {
+              size_t scratch_bytes, bool built_in, void* stream) {
   Shape s;
   const int rc = check_params(params, &s, true);
   if (rc != S2O_OK) return rc;
@@ -81,6 +83,12 @@ int plan_call(const void* Q, const void* K, const s2o_params* params, const s2o_
       misaligned(out->kv_perm, 16) || misaligned(out->s_k, 16) || misaligned(out->status, 4))
     return S2O_EINVAL;
   const size_t need = s2o::plan_scratch_bytes(s.Z, s.H, s.Hkv, s.L, s.S, s.nc);
+  if (built_in) {
+    if (need > s2o::kStaticPlanScratchBytes) return S2O_ESCRATCH;   // before any HIP call
+    const hipError_t e = s2o::static_plan_scratch(&scratch);
+    if (e != hipSuccess) return hip_fail(e);
+    scratch_bytes = s2o::kStaticPlanScratchBytes;
+  }
   if (!scratch || misaligned(scratch, 256) || scratch_bytes < need) return S2O_ESCRATCH;
 
   s2o::PlanArgs a;
@@ -108,7 +116,7 @@ const char* s2o_strerror(int code) {
     case S2O_OK: return "ok";
     case S2O_EINVAL: return "invalid argument";
     case S2O_EUNSUPPORTED: return "unsupported configuration (need D=128, B_M in {64,128}, B_N=64, S%B_M==0; s2o_plan: S<=8192; no own-segment pass when non_causal)";
-    case S2O_ESCRATCH: return "scratch buffer missing, misaligned or too small";
+    case S2O_ESCRATCH: return "scratch buffer missing, misaligned or too small (s2o_plan_static: the configuration needs more than the built-in S2O_STATIC_SCRATCH_BYTES)";
     case S2O_EHIP: return "HIP runtime error (see s2o_last_hip_error)";
     default: return "unknown error code";
   }
@@ -136,7 +144,12 @@ int s2o_plan_sizes(const s2o_params* params, size_t* q_perm_bytes, size_t* kv_pe
 
 int s2o_plan(const void* Q, const void* K, const s2o_params* params, const s2o_plan_out* out,
              void* scratch, size_t scratch_bytes, void* stream) {
-  return plan_call(Q, K, params, out, scratch, scratch_bytes, stream);
+  return plan_call(Q, K, params, out, scratch, scratch_bytes, false, stream);
+}
+
+int s2o_plan_static(const void* Q, const void* K, const s2o_params* params, const s2o_plan_out* out,
+                    void* stream) {
+  return plan_call(Q, K, params, out, nullptr, 0, true, stream);
 }
 
 int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* scratch_bytes) {

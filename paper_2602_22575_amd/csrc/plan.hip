@@ -141,6 +141,33 @@ size_t plan_scratch_bytes(int Z, int H, int Hkv, int L, int S, int non_causal) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Built-in scratch for callers that cannot allocate (s2o_plan_static): one array per GPU, held
+// from the moment the library is loaded there until the process ends.  The name below is a
+// host-side stand-in, not a device address: host code only ever uses the address that
+// hipGetSymbolAddress reports for the current device.
+static __device__ __align__(256) unsigned char scratch[kStaticPlanScratchBytes];
+
+hipError_t static_plan_scratch(void** ptr) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* addr[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    addr[dev] = p;
+  }
+  *ptr = addr[dev];
+  return hipSuccess;
+}
+
+// ---------------------------------------------------------------------------------------
 __global__ void init_kernel(Scratch s, int64_t rows, int32_t* status) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < 16) s.counters[i] = 0;

@@ -79,6 +79,10 @@ struct PlanArgs {
 };
 
 size_t plan_scratch_bytes(int Z, int H, int Hkv, int L, int S, int non_causal);
+// Size of the library's built-in plan scratch (S2O_STATIC_SCRATCH_BYTES of the C header) and its
+// device address on the current GPU.
+constexpr size_t kStaticPlanScratchBytes = (size_t)32 << 20;
+hipError_t static_plan_scratch(void** ptr);
 size_t attention_state_bytes(int Z, int H, int L);
 hipError_t launch_plan(const PlanArgs& a, hipStream_t stream);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t stream);
