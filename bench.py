@@ -20,8 +20,67 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published, at 2.4 GHz)
 PEAK_HBM_GBS = 8000.0
+BF16_FLOP_PER_CLK = 256 * 4 * 1024   # 256 CUs x 4 SIMDs x 1024 FLOP per clock (a 32x32x16 MFMA takes 32 clocks)
+
+
+def kernel_source_id():
+    """Short hash of the kernel sources this library was built from (csrc/ and the header): a
+    counter measurement on file is only quoted while it was taken on the same sources."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(ROOT, "paper_2602_22575_amd", "csrc", "*.hip"))
+                   + glob.glob(os.path.join(ROOT, "paper_2602_22575_amd", "csrc", "*.h"))
+                   + [os.path.join(ROOT, "include", "s2o.h")])
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:12]
+
+
+class ClockSampler:
+    """Samples the shader clock the driver reports (pp_dpm_sclk, the level marked '*') while a
+    stage runs; None where the file cannot be read."""
+
+    def __init__(self):
+        import glob
+        files = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.path = files[0] if files else None
+        self.samples = []
+        self._stop = False
+        self._thread = None
+
+    def _read(self):
+        try:
+            for line in open(self.path):
+                if line.rstrip().endswith("*"):
+                    return float(line.split(":")[1].strip().split("Mhz")[0])
+        except Exception:
+            return None
+        return None
+
+    def __enter__(self):
+        import threading
+        if self.path is not None:
+            def loop():
+                while not self._stop:
+                    v = self._read()
+                    if v is not None:
+                        self.samples.append(v)
+                    time.sleep(0.002)
+            self._thread = threading.Thread(target=loop, daemon=True)
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        if self._thread is not None:
+            self._thread.join()
+
+    def median_mhz(self):
+        return float(np.median(self.samples)) if self.samples else None
 
 
 def local_tiles(w):
@@ -58,10 +117,16 @@ def tile_flops(w, computed, skipped):
 def recorded_traffic(workload, tau, block_m, kernel):
     """HBM bytes per launch of `kernel` measured with rocprofv3 PMC counters (FETCH_SIZE and
     WRITE_SIZE runs, scaled against a copy kernel of known size) for exactly this workload,
-    threshold and tiling, as recorded in the TRAFFIC lines of profiles/*.txt; None if no
-    such measurement is on file (counters cannot be read from inside this process)."""
+    threshold and tiling, as recorded in the TRAFFIC lines of profiles/*.txt, and where the
+    figure comes from: (bytes, {"file", "commit", "src", "stale"}).  A line records the commit
+    and the kernel-source hash (kernel_source_id) it was measured at; when the sources have
+    changed since, the figure no longer describes this library: bytes is None and stale is true.
+    (None, None) if no such measurement is on file (counters cannot be read from inside this
+    process)."""
     import glob
     want = {"workload": workload, "tau": repr(float(tau)), "block_m": str(block_m), "kernel": kernel}
+    here = kernel_source_id()
+    found = None
     for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
         for line in open(path):
             if not line.startswith("TRAFFIC "):
@@ -72,8 +137,13 @@ def recorded_traffic(workload, tau, block_m, kernel):
             except ValueError:
                 continue
             if all(kv.get(k) == v for k, v in want.items()):
-                return float(kv["bytes"])
-    return None
+                stale = kv.get("src") != here
+                src = {"file": os.path.relpath(path, ROOT), "commit": kv.get("commit"), "src": kv.get("src"),
+                       "stale": stale}
+                if not stale:
+                    return float(kv["bytes"]), src
+                found = (None, src)
+    return found if found is not None else (None, None)
 
 
 def plan_bytes(w):
@@ -92,7 +162,8 @@ def main():
     ap.add_argument("--tau", type=float, default=5e-3)
     ap.add_argument("--block-m", type=int, default=None, help="query tile rows (64 or 128); default: the workload's")
     ap.add_argument("--seg-len", type=int, default=None, help="segment length S; default: the workload's (2048 at 128K)")
-    ap.add_argument("--sweep", action="store_true", help="also time every tau of the workload")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip the threshold sweep (every tau of the workload: ms, density, TFLOP/s, MSE vs dense)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mse", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -206,13 +277,17 @@ def main():
         attn_fn = lambda tau, out=O: s2o.s2o_attention(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau, O=out,
                                                        computed=comp, skipped=skip, two_pass=False)
         local_ms = local_mean = None
-        prefix_ms, prefix_mean = stage(lambda: attn_fn(args.tau))
+        with ClockSampler() as clk:
+            prefix_ms, prefix_mean = stage(lambda: attn_fn(args.tau))
+        sclk_mhz = clk.median_mhz()
         attn_ms = prefix_ms
     else:
         local_ms, local_mean = stage(lambda: s2o.s2o_attention_local(Qd, Kd, Vd, params, scratch=state))
         attn_fn = lambda tau, out=O: s2o.s2o_attention_prefix(Qd, Kd, Vd, params, plan.q_perm, plan.kv_perm, tau,
                                                               state, O=out, computed=comp, skipped=skip)
-        prefix_ms, prefix_mean = stage(lambda: attn_fn(args.tau))
+        with ClockSampler() as clk:
+            prefix_ms, prefix_mean = stage(lambda: attn_fn(args.tau))
+        sclk_mhz = clk.median_mhz()
         attn_ms = local_ms + prefix_ms
     c, s = comp.cpu().numpy(), skip.cpu().numpy()
     flops, trig = tile_flops(w, c, s)
@@ -238,7 +313,8 @@ def main():
         return float(np.mean(per_head)), num / den
 
     Od = None
-    if not args.no_mse or args.sweep:
+    do_sweep = not args.no_sweep and not args.no_mse
+    if not args.no_mse:
         O_tau = O.clone()
         Od = torch.empty_like(O)
         dense_ms = float(np.mean(timed(lambda: attn_fn(0.0, Od), 2))) + (local_ms or 0.0)
@@ -247,15 +323,19 @@ def main():
         extra["dense_tau0_tflops"] = 4.0 * w.BM * w.BN * w.D * (w.L // w.BM) * (w.L // w.BM + 1) / 2 * w.Z * w.H \
             / (dense_ms * 1e-3) / 1e12
         del O_tau
-    if args.sweep:
+    if do_sweep:
+        # compact: one record per threshold, [tau, attention ms (own-segment pass + walk), density,
+        # TFLOP/s on computed blocks, MSE vs the tau=0 output, relative MSE]
         sweep = []
         for tau in w.taus:
-            ms = float(np.mean(timed(lambda: attn_fn(tau), 3))) + (local_ms or 0.0)
+            ms = float(np.median(timed(lambda: attn_fn(tau), 3))) + (local_ms or 0.0)
             cc, ss = comp.cpu().numpy(), skip.cpu().numpy()
             f, _ = tile_flops(w, cc, ss)
             mse, rel = mse_of(O, Od)
-            sweep.append(dict(tau=tau, attn_ms=ms, density=float(density_of(w, ss).mean()),
-                              tflops=f / (ms * 1e-3) / 1e12, mse_vs_dense=mse, rel_mse_vs_dense=rel))
+            sweep.append([tau, round(ms, 3), round(float(density_of(w, ss).mean()), 5),
+                          round(f / (ms * 1e-3) / 1e12, 1), float(f"{mse:.4g}"), float(f"{rel:.4g}")])
+        extra["tau_sweep_columns"] = ["tau", "attn_ms", "density", "tflops_on_computed_blocks", "mse_vs_dense",
+                                      "rel_mse_vs_dense"]
         extra["tau_sweep"] = sweep
     del Od
 
@@ -264,6 +344,9 @@ def main():
         cpu = cpu_baseline(w, Qb, Kb, Vb, plan, args.tau, float((w.N * (w.N - 1) // 2) * (w.S // w.BN)
                                                                  * (w.S // w.BM) * w.Z * w.H - s.sum()))
 
+    walk_traffic, walk_source = (None, None) if args.fused else recorded_traffic(w.name, args.tau, w.BM,
+                                                                                  "s2o_prefix_kernel")
+    plan_traffic, plan_source = recorded_traffic(w.name, args.tau, w.BM, "s2o_plan")
     out = {
         "metric": "128K prefill attn ms/layer, TFLOP/s on computed blocks, MSE vs dense at sparsity",
         "value_is": "ms per layer of the whole hot path: ranking (plan) + own-segment pass + prefix walk",
@@ -285,8 +368,20 @@ def main():
                      "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": dom_tflops / PEAK_BF16_TFLOPS, "ms_per_launch": prefix_ms,
                      "flops_per_launch": dom_flops,
-                     "traffic": None if args.fused else recorded_traffic(w.name, args.tau, w.BM,
-                                                                         "s2o_prefix_kernel")},
+                     # the same peak at the shader clock the driver reported while this kernel ran
+                     "sclk_mhz": sclk_mhz,
+                     "peak_at_sclk": None if sclk_mhz is None else BF16_FLOP_PER_CLK * sclk_mhz * 1e6 / 1e12,
+                     "frac_at_sclk": None if sclk_mhz is None else
+                     dom_tflops / (BF16_FLOP_PER_CLK * sclk_mhz * 1e6 / 1e12),
+                     "traffic": walk_traffic, "traffic_source": walk_source},
+        "plan_roofline": {"bound": "hbm", "kernel": "s2o_plan (all its kernels)", "unit": "GB/s",
+                          "algorithmic_bytes": plan_bytes(w), "ms_per_launch": plan_ms,
+                          "achieved": plan_bytes(w) / (plan_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                          "frac": plan_bytes(w) / (plan_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                          "traffic": plan_traffic, "traffic_source": plan_source,
+                          "frac_counter_bytes": None if plan_traffic is None else
+                          plan_traffic / (plan_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+        "kernel_source_id": kernel_source_id(),
         "cpu_baseline": cpu,
         "paper_context": "other hardware, context only: the paper reports 7.51x (7.53x in the text) attention speed-up over "
                          "FlashAttention-2 and 3.82x lower MSE at matched sparsity on 'NVIDIA GPUs' (Triton, 128x128 tiles, "

@@ -151,7 +151,14 @@ int s2o_attention_sizes(const s2o_params* params, size_t* counts_bytes, size_t* 
 /* Step 2 (Alg. 2 + Alg. 3, or Alg. 4 when use_q_perm == 0).
  *   q_perm   [Z,H,N,S] as produced by s2o_plan; ignored (may be NULL) if use_q_perm == 0.
  *   kv_perm  packed prefix rows; any permutation of [0, n*S) per row is legal (the maps
- *            need not come from s2o_plan).  Entries are clamped to [0, L).
+ *            need not come from s2o_plan).  Entries are clamped to [0, L), so a bad map cannot
+ *            make the kernels read outside K and V, but a token >= n*S in the row of segment n
+ *            would silently break causality.  Debug switch: with the environment variable
+ *            S2O_VALIDATE_MAPS set (to anything but "0") every call that walks a prefix first
+ *            checks on the device that all q_perm entries lie in [0, S) and all kv_perm
+ *            entries of segment n in [0, n*S) ([0, L) when non_causal) and returns S2O_EINVAL
+ *            otherwise; that check allocates a word of device memory and synchronises
+ *            `stream`, so it is not for production loops or graph capture.
  *   tau      early-stop threshold.  Query tile j of segment n walks its prefix row in
  *            tiles of B_N tokens; with mass_i = sum over the tile of exp(x_it - m'_i) and
  *            prev_i = l_i * exp(m_i - m'_i) (the old normaliser in the new scale) the

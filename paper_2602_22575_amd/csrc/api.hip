@@ -4,6 +4,8 @@
 #include <string.h>
 
 #include "../../include/s2o.h"
+
+#include <stdlib.h>
 #include "s2o_internal.h"
 
 namespace {
@@ -214,6 +216,16 @@ int attention_call(int passes, const void* Q, const void* K, const void* V, cons
   a.scale_log2e = scale * 1.4426950408889634f;
   for (int i = 0; i < 3; ++i) {
     a.qs[i] = s.qs[i]; a.ks[i] = s.ks[i]; a.vs[i] = s.vs[i]; a.os[i] = s.os[i];
+  }
+  if (walk) {
+    // debug switch: check the maps' ranges on the device before they are used
+    const char* v = getenv("S2O_VALIDATE_MAPS");
+    if (v && v[0] && v[0] != '0') {
+      int bits = 0;
+      const hipError_t ve = s2o::validate_maps(a, (hipStream_t)stream, &bits);
+      if (ve != hipSuccess) return hip_fail(ve);
+      if (bits) return S2O_EINVAL;
+    }
   }
   const hipError_t e = s2o::launch_attention(a, (hipStream_t)stream);
   return e == hipSuccess ? S2O_OK : hip_fail(e);

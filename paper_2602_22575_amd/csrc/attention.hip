@@ -288,6 +288,55 @@ size_t attention_state_bytes(int Z, int H, int L) {
   return (size_t)Z * H * L * (kD + 2) * sizeof(float);
 }
 
+// ---- debug check of the caller's maps (S2O_VALIDATE_MAPS): bit 0 = a Q_perm entry outside
+// [0, S), bit 1 = a KV_perm entry of segment n outside its row's range ([0, n*S); [0, L) without
+// causality).  Permutation-ness is not checked.
+__global__ __launch_bounds__(256) void validate_maps_kernel(const AttnArgs a, int32_t* flag) {
+  const int64_t zh = blockIdx.y;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int bad = 0;
+  if (a.use_q_perm && a.q_perm) {
+    const int32_t* q = a.q_perm + zh * a.L;
+    for (int64_t i = first; i < a.L; i += stride) bad |= (q[i] < 0 || q[i] >= a.S) ? 1 : 0;
+  }
+  if (a.kv_perm) {
+    const int64_t total = kv_rows_total(a.N, a.S, a.L, a.non_causal);
+    const int32_t* kv = a.kv_perm + zh * total;
+    for (int64_t i = first; i < total; i += stride) {
+      // segment of packed position i: the largest n with kv_row_start(n) <= i
+      int n;
+      if (a.non_causal) {
+        n = (int)(i / a.L);
+      } else {
+        n = (int)((1.0 + sqrt(1.0 + 8.0 * (double)(i / a.S))) * 0.5);
+        while (kv_row_start(n, a.S, a.L, 0) > i) --n;
+        while (kv_row_start(n + 1, a.S, a.L, 0) <= i) ++n;
+      }
+      const int64_t lim = kv_row_len(n, a.S, a.L, a.non_causal);
+      bad |= (kv[i] < 0 || kv[i] >= lim) ? 2 : 0;
+    }
+  }
+  if (bad) atomicOr(flag, bad);
+}
+
+hipError_t validate_maps(const AttnArgs& a, hipStream_t stream, int* bits) {
+  int32_t* flag = nullptr;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&flag), sizeof(int32_t));
+  if (e != hipSuccess) return e;
+  int32_t h = 0;
+  e = hipMemcpyAsync(flag, &h, sizeof(h), hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(validate_maps_kernel, dim3(64, (unsigned)(a.Z * a.H)), dim3(256), 0, stream, a, flag);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipMemcpyAsync(&h, flag, sizeof(h), hipMemcpyDeviceToHost, stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);
+  (void)hipFree(flag);
+  *bits = h;
+  return e;
+}
+
 hipError_t launch_attention(const AttnArgs& a, hipStream_t stream) {
   if (a.passes != 0) {                 // separate kernels through the state buffers
     if (a.passes & 1) {

@@ -40,10 +40,30 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_local_kernel(const AttnArgs a
   const int JG = (a.S + kRowsPerWg - 1) / kRowsPerWg;   // row blocks of 128 per (z,h,n)
   const int PG = (JG + 1) / 2;                          // workgroups per (z,h,n): a long and a short block each
 
-  int zh_, nr, pos;
-  map_block(blockIdx.x, a.Z * a.H, PG, zh_, nr, pos);
-  const int n = a.N - 1 - nr, z = zh_ / a.H, h = zh_ % a.H;
-  const int g = h / G;
+  // Workgroup -> (z, KV head, segment, query head of the group, pos).  Every (z, KV head, segment)
+  // is one unit of G * PG workgroups with consecutive ids on one XCD (block ids are dealt
+  // round-robin to the 8 XCDs), the G query heads of the group interleaved: they read the same
+  // 2 * S rows of K and V at about the same time, so the segment is fetched from HBM once per
+  // group instead of once per query head.  All units cost the same here (no early stop), so
+  // nothing needs balancing across XCDs.
+  int z, g, n, h, pos;
+  {
+    const int per_unit = G * PG, U = a.Z * a.Hkv * a.N, b = blockIdx.x;
+    int u, within;
+    if (U % 8 == 0) {
+      const int xcd = b & 7, idx = b >> 3;
+      u = (idx / per_unit) * 8 + xcd;
+      within = idx % per_unit;
+    } else {
+      u = b / per_unit;
+      within = b % per_unit;
+    }
+    pos = within / G;
+    n = u % a.N;
+    g = (u / a.N) % a.Hkv;
+    z = u / (a.N * a.Hkv);
+    h = g * G + within % G;
+  }
   const uint16_t* Qh = a.Q + z * a.qs[0] + h * a.qs[1];
   const uint16_t* Kh = a.K + z * a.ks[0] + g * a.ks[1];
   const uint16_t* Vh = a.V + z * a.vs[0] + g * a.vs[1];

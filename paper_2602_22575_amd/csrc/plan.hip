@@ -118,7 +118,8 @@ static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S, int non_ca
   while (s.cell > 256 && rows * (((non_causal ? L : L / 2) + s.cell - 1) / s.cell) < 2048) s.cell /= 2;
   s.maxch = (L + s.cell - 1) / s.cell;
   size_t off = 0;
-  auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return (char*)base + o; };
+  // (integer arithmetic: the size query carves from a null base)
+  auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return (char*)((uintptr_t)base + o); };
   s.kguide = (float*)take((size_t)Z * Hkv * 8 * kD * 4);
   s.qmean = (float*)take((size_t)rows * kD * 4);
   s.qsplit = (uint16_t*)take((size_t)rows * 3 * kD * 2);

@@ -86,6 +86,8 @@ hipError_t static_plan_scratch(void** ptr);
 size_t attention_state_bytes(int Z, int H, int L);
 hipError_t launch_plan(const PlanArgs& a, hipStream_t stream);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t stream);
+// Debug check of q_perm / kv_perm ranges (allocates, synchronises `stream`); bits: 1 = Q_perm, 2 = KV_perm
+hipError_t validate_maps(const AttnArgs& a, hipStream_t stream, int* bits);
 // Alg. 2 alone (local.hip): own-segment pass in original query order into the state buffers
 hipError_t launch_local(const AttnArgs& a, hipStream_t stream);
 // Alg. 3 alone (prefix.hip): prefix walk in permuted query order from the state buffers

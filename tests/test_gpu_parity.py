@@ -315,6 +315,38 @@ def test_separate_passes_equal_the_combined_call(tiny):
     assert torch.equal(O1.view(torch.int16), O4.view(torch.int16)) and torch.equal(c1, c4)
 
 
+def test_map_validation_switch(tiny, monkeypatch):
+    """S2O_VALIDATE_MAPS: a KV_perm entry that breaks causality (token n*S in the row of segment
+    n: inside K and V, so harmless to read) or a Q_perm entry outside the segment is refused
+    with S2O_EINVAL; the plan's own maps pass."""
+    import torch
+    import paper_2602_22575_amd as s2o
+    w, _, (Qd, Kd, Vd) = tiny
+    p = gu.params_for(w)
+    plan = s2o.s2o_plan(Qd, Kd, p, want_scores=False)
+    state = s2o.s2o_attention_local(Qd, Kd, Vd, p)
+    monkeypatch.setenv("S2O_VALIDATE_MAPS", "1")
+    _say("case: map validation, plan maps")
+    s2o.s2o_attention_prefix(Qd, Kd, Vd, p, plan.q_perm, plan.kv_perm, 0.05, state)
+    torch.cuda.synchronize()
+    n = 3
+    bad_kv = plan.kv_perm.clone()
+    bad_kv[0, 0, orc.kv_row_offset(n, w.S) + 17] = n * w.S           # first token of segment n itself
+    _say("case: map validation, KV_perm entry outside its prefix")
+    with pytest.raises(s2o.S2OError) as e:
+        s2o.s2o_attention_prefix(Qd, Kd, Vd, p, plan.q_perm, bad_kv, 0.05, state)
+    assert e.value.code == s2o.binding.S2O_EINVAL
+    bad_q = plan.q_perm.clone()
+    bad_q[0, 0, 1, 5] = w.S
+    _say("case: map validation, Q_perm entry outside the segment")
+    with pytest.raises(s2o.S2OError) as e:
+        s2o.s2o_attention(Qd, Kd, Vd, p, bad_q, plan.kv_perm, 0.05, two_pass=False)
+    assert e.value.code == s2o.binding.S2O_EINVAL
+    monkeypatch.setenv("S2O_VALIDATE_MAPS", "0")
+    s2o.s2o_attention_prefix(Qd, Kd, Vd, p, plan.q_perm, bad_kv, 0.05, state)   # switch off: not looked at
+    torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("L,S,H,Hkv", [(256, 256, 1, 1), (128, 64, 2, 1), (1536, 192, 4, 2), (2048, 1024, 2, 2)])
 def test_edge_shapes(gpu, L, S, H, Hkv):
     """Single segment (no prefix at all), a one-tile segment (three idle wavefronts), a
