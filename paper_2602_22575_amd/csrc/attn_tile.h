@@ -338,6 +338,21 @@ __device__ __forceinline__ void abandon_v_fragments(u32x2 (&vf)[16][2]) {
   static_for<0, kVEarly>([&](auto c_) { lds_wait<0>(vf[decltype(c_)::value][0], vf[decltype(c_)::value][1]); });
 }
 
+// O^T accumulate step with the accumulator updated in place.  As a builtin the compiler is free
+// to give the result a tuple of its own, and for the loop-carried 64-register accumulator it
+// does: a copy of O^T (32 two-register moves) per key tile.  In assembly the operand is tied.
+// The compiler then no longer sees an MFMA and inserts no wait states around it.  In front: an
+// MFMA must not read a register in the two issue slots after a VALU instruction wrote it, and
+// the compiler does place moves of the operands right before the statement -- hence the two
+// idle slots.  Behind: the next MFMA on the same accumulator needs none; before anything else
+// reads or writes the accumulator, mfma_settle() must have run.
+__device__ __forceinline__ void mfma_acc(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_settle(f32x16 (&o)[4]) {
+  asm volatile("s_nop 15\n\ts_nop 3" : "+v"(o[0]), "+v"(o[1]), "+v"(o[2]), "+v"(o[3]));
+}
+
 // O^T += V^T P^T.  kEarly: fragments 0..kVEarly-1 were requested by qk_tile_sched.
 template <int kVOff, bool kEarly>
 __device__ __forceinline__ void pv_tile_sched(const OperandAddr& oa, const bf16x8 (&pb)[4], f32x16 (&o)[4],
@@ -349,9 +364,10 @@ __device__ __forceinline__ void pv_tile_sched(const OperandAddr& oa, const bf16x
     constexpr int frags = (c + kVAhead < 16 ? c + kVAhead : 16);
     lds_wait<2 * frags - (2 * c + 2)>(vf[c][0], vf[c][1]);
     const u32x4 w = {vf[c][0].x, vf[c][0].y, vf[c][1].x, vf[c][1].y};
-    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), pb[st], o[db], 0, 0, 0);
+    mfma_acc(o[db], __builtin_bit_cast(bf16x8, w), pb[st]);
     if constexpr (c + kVAhead < 16) issue_v_fragment<kVOff, c + kVAhead>(oa, vf);
   });
+  mfma_settle(o);
 }
 
 // The same two products for a step that does them back to back (PV right after its scores).
@@ -448,7 +464,13 @@ __device__ __forceinline__ void rescale(f32x16 (&o)[4], float al, bool gr) {
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) o[db][i] *= al;
+      for (int i = 0; i < 16; ++i) {
+        // in place: as plain C++ the products get registers of their own and the common path
+        // (no rescale) pays for the merge with a copy of the whole accumulator per key tile
+        float x = o[db][i];
+        asm volatile("v_mul_f32 %0, %1, %0" : "+v"(x) : "v"(al));
+        o[db][i] = x;
+      }
   }
 }
 

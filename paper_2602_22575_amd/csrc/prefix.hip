@@ -252,19 +252,30 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
       publish(0);
       end_step();
       bool pending = true;                      // a scored tile waits for its vote
-      // one step; tile `it` has parity P: K(it) sits in K buffer P, V(it-1) in V buffer 1-P.
+      // One step.  K(it) sits in K buffer it & 1, V(it-1) in V buffer (it-1) & 1: the operand
+      // addresses `fa` carry the current buffers (five additions per step), so one loop body
+      // serves both parities -- two bodies with the buffer as a constant get the accumulator
+      // different registers and pay a 32-move shuffle between them on every step.
       // Returns false when the query tile stops at this step.
-      auto step = [&](auto par_, int it_) -> bool {
-        constexpr int P = decltype(par_)::value;
+      OperandAddr fa;
+      auto aim = [&](int it_) {               // fa <- buffers of step it_
+        const uint32_t kb = (uint32_t)(kKBytes0 + (it_ & 1) * kTileBytes);
+        const uint32_t vb = (uint32_t)(kVBytes0 + ((it_ - 1) & 1) * kTileBytes);
+        fa.k0 = oa.k0 + kb;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) fa.v[db] = oa.v[db] + vb;
+      };
+      auto step = [&](int it_) -> bool {
         const int* vf = vote_flags(it_ - 1);
         const int votes = tile_votes(vf);
+        aim(it_);
         if (votes == 0) {
           const int any = wg_votes(vf);
           if (a.stop_mode == 0) {
             l_run = l_save; m_ref = m_save;
           } else {
             rescale(o, alpha_pend, grow_pend);
-            pv_tile_only<kVBytes0 + (1 - P) * kTileBytes>(oa, pb_pend, o);
+            pv_tile_only<0>(fa, pb_pend, o);
             ++committed;
           }
           pending = false;
@@ -273,9 +284,9 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
         }
         fetch_step(it_);
         u32x2 vfr[16][2];
-        qk_tile_sched<kKBytes0 + P * kTileBytes, kVBytes0 + (1 - P) * kTileBytes, true>(oa, qf, s, vfr);
+        qk_tile_sched<0, 0, true>(fa, qf, s, vfr);
         rescale(o, alpha_pend, grow_pend);
-        pv_tile_sched<kVBytes0 + (1 - P) * kTileBytes, true>(oa, pb_pend, o, vfr);
+        pv_tile_sched<0, true>(fa, pb_pend, o, vfr);
         ++committed;
         softmax();
         publish(it_);
@@ -283,21 +294,16 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
         __syncthreads();
         return true;
       };
-      for (it = 1; it < ntiles;) {
-        if (!step(Par<1>{}, it)) break;
-        ++it;
-        if (it >= ntiles) break;
-        if (!step(Par<0>{}, it)) break;
-        ++it;
-      }
+      for (it = 1; it < ntiles; ++it)
+        if (!step(it)) break;
       if (pending) {                            // the last tile: its vote is visible now
         const bool stop = tile_votes(vote_flags(ntiles - 1)) == 0;
         if (stop && a.stop_mode == 0) {
           l_run = l_save; m_ref = m_save;
         } else {
           rescale(o, alpha_pend, grow_pend);
-          if ((ntiles - 1) & 1) pv_tile_only<kVBytes0 + kTileBytes>(oa, pb_pend, o);
-          else pv_tile_only<kVBytes0>(oa, pb_pend, o);
+          aim(ntiles);                          // V(ntiles-1)
+          pv_tile_only<0>(fa, pb_pend, o);
           ++committed;
         }
         wg_done = true;
