@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Two measurement studies on one MI355X, printed as Markdown tables.
+"""Measurement studies on one MI355X, printed as Markdown tables.
 
   python -m paper_2602_22575_amd.studies abcd         overhead decomposition (paper App. A,
       "Why Online Permutation Adds Negligible Overhead", kernels A-D): the same dense amount
@@ -25,6 +25,13 @@
   python -m paper_2602_22575_amd.studies qperm        with and without the query permutation
       (paper's component ablation and "Single-pass Variant"): time, density and MSE against
       the dense output, for the two-launch form, the fused launch, and original query order.
+
+  python -m paper_2602_22575_amd.studies power        is the prefix walk limited by its instruction
+      schedule or by the chip's power budget?  The same dense walk (tau = 0: every tile folded
+      in, identical instruction stream) on the workload's Gaussian data, with V zeroed, and with
+      Q, K and V all zero, with the shader clock the driver reports sampled meanwhile: equal
+      time x clock products with very different clocks mean the cycle count is fixed and the
+      clock is what the data's switching activity leaves of the power budget.
 
 Inputs are the seeded synthetic workloads of inputs.py; every figure is the mean of a few
 launches timed with events on the launch stream.
@@ -254,6 +261,57 @@ def mixed():
         torch.cuda.empty_cache()
 
 
+def power():
+    import glob
+    import threading
+    import time
+    import torch
+    from . import binding as s2o, inputs
+    w = inputs.workload("llama128k")
+    Qd, Kd, Vd = (_dev(x) for x in inputs.make_qkv(w))
+    p = s2o.make_params(w.Z, w.H, w.Hkv, w.L, w.D, w.S, w.BM, w.BN)
+    plan = s2o.s2o_plan(Qd, Kd, p, want_scores=False)
+    state = torch.empty(s2o.s2o_attention_sizes(p)["scratch"], dtype=torch.uint8, device="cuda:0")
+    O = torch.empty_like(Qd)
+    files = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+
+    def sclk():
+        try:
+            for line in open(files[0]):
+                if line.rstrip().endswith("*"):
+                    return float(line.split(":")[1].strip().split("Mhz")[0])
+        except Exception:
+            return None
+        return None
+
+    dense_flops = 4.0 * w.BM * w.BN * w.D * sum(n * (w.S // w.BN) * (w.S // w.BM) for n in range(w.N)) * w.Z * w.H
+    print(f"workload {w.name}: dense prefix walk (tau = 0, ranked maps of the real data in every case), 64x64 tiles")
+    print("| data | ms | TFLOP/s | shader clock MHz (median of samples) | ms x GHz |")
+    print("|---|---|---|---|---|")
+    zero = lambda t: torch.zeros_like(t)
+    for name, (q_, k_, v_) in (("Gaussian Q, K, V (the workload)", (Qd, Kd, Vd)),
+                               ("Gaussian Q, K; V = 0", (Qd, Kd, zero(Vd))),
+                               ("Q = K = V = 0", (zero(Qd), zero(Kd), zero(Vd))),
+                               ("Gaussian Q, K, V again", (Qd, Kd, Vd))):
+        s2o.s2o_attention_local(q_, k_, v_, p, scratch=state)
+        torch.cuda.synchronize()
+        samples, stop = [], [False]
+
+        def loop():
+            while not stop[0]:
+                v = sclk() if files else None
+                if v:
+                    samples.append(v)
+                time.sleep(0.002)
+        th = threading.Thread(target=loop)
+        th.start()
+        ms = _timed(lambda: s2o.s2o_attention_prefix(q_, k_, v_, p, plan.q_perm, plan.kv_perm, 0.0, state, O=O), 3)
+        stop[0] = True
+        th.join()
+        mhz = float(np.median(samples)) if samples else float("nan")
+        print(f"| {name} | {ms:.2f} | {dense_flops / (ms * 1e-3) / 1e12:.0f} | {mhz:.0f} | {ms * mhz / 1e3:.1f} |", flush=True)
+
+
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else ""
     if what == "abcd":
@@ -266,6 +324,8 @@ if __name__ == "__main__":
         mixed()
     elif what == "qperm":
         qperm()
+    elif what == "power":
+        power()
     else:
         print(__doc__)
         sys.exit(2)
