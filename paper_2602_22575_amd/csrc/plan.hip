@@ -13,15 +13,21 @@
 //                        The Argsort of a prefix row (up to L - S scores) is a sample sort:
 //                        buckets are delimited by splitters taken from a sorted sample of
 //                        the row, so their populations are balanced for any distribution.
-//   count_kernel         per (row, cell of up to 4096 tokens): bucket counts, kept in LDS and
-//                        written once per cell (no global atomics).
-//   scatter_kernel       per (row, cell): (key, token) pairs to their bucket -- offset of the
-//                        (row, cell, bucket) run + a rank from an LDS cursor -- staged in LDS
-//                        sorted by bucket so that the global stores are runs, not scatters.
 //   splitter_kernel      per prefix row: sorts the sample in LDS and keeps every
 //                        (sample size / buckets)-th value as a splitter.
-//   scan_kernel          per prefix row: run offsets (bucket-major, cell-minor) and the
-//                        list of spans (runs of consecutive buckets that fit the LDS sort).
+//   scatter_kernel       per (row, cell of up to 1024 tokens): (key, token) pairs to their
+//                        bucket.  Every bucket of a row owns a region of twice the average
+//                        population; the cell counts its buckets in LDS, claims a run in each
+//                        region with one atomic add on the row's cursor, and writes its pairs
+//                        staged in LDS sorted by bucket, so that the global stores are runs,
+//                        not scatters.  No counting pass over the scores, no offset scan.
+//   span_kernel          per prefix row: the final cursors are the bucket populations; cuts
+//                        them into spans (runs of consecutive buckets that fit the LDS sort).
+//   count_kernel, scan_exact_kernel, scatter_exact_kernel
+//                        the exact path for rows in which a bucket outgrew its region (many
+//                        equal scores): bucket counts per cell, run offsets (bucket-major,
+//                        cell-minor), scatter to a compact layout.  They loop over a list of
+//                        such rows, which is normally empty.
 //   span_sort_kernel     sorts each span in LDS and writes the token indices at their
 //                        final ranks -> KV_perm.  Linear-time: a second, fine bucketing on
 //                        the score value leaves a few keys per sub-bucket, which are ranked by
@@ -54,10 +60,30 @@ constexpr int kCellMax = 1024;     // key tokens per (row, cell) of the bucket c
 constexpr int kSub = 64;           // key tokens per LDS tile of the score kernel (32 in the scatter pass)
 constexpr int kKStride = 136;      // bf16 elements per K row in LDS (272 B)
 constexpr int kBigGrid = 64;       // workgroups of the fallback sort
+constexpr int kRedoGrid = 2048;    // workgroups of the exact path's kernels (they loop over the redo list)
 
 __host__ __device__ inline int row_buckets(int64_t len) {
   const int64_t nb = len / kBucketAvg;
   return nb < 1 ? 1 : (nb > kNBMax ? kNBMax : (int)nb);
+}
+
+// Layout of the (key, token) pairs between the scatter and the sorts.  Every bucket of a row owns
+// a region of bucket_cap(len) slots, twice the average population, and the workgroups of the
+// scatter claim runs inside it from a cursor, so no counting pass over the scores is needed to
+// find a run's place.  (The splitters are every 32nd value of a sorted 1-in-64 sample, so a
+// bucket's population scatters like a Gamma(32) variable around the mean, sigma = 18 %: twice
+// the mean is 5.7 sigma away; one and a half times would send one row in five to the exact
+// path.)  A row in which some bucket does outgrow its region -- many equal scores -- is laid out
+// again by the exact path (count, offsets, scatter), compactly, from the start of its regions.
+// region_base(n): first slot of row n inside its head, a closed-form upper bound of the sum of
+// the earlier rows' regions (nb * cap < 2 * len + 16 * nb; regions start on 128-byte
+// boundaries).
+__host__ __device__ inline uint32_t bucket_cap(int64_t len) {
+  const int64_t avg = len / row_buckets(len);
+  return (uint32_t)((2 * avg + 15) & ~(int64_t)15);
+}
+__host__ __device__ inline int64_t region_base(int64_t n, int64_t S, int64_t L, int nc) {
+  return nc ? n * (2 * L + 16 * kNBMax) : 2 * kv_row_offset(n, S) + n * 16 * kNBMax;
 }
 
 // float -> uint32 whose unsigned order is the float order (-0 canonicalised to +0)
@@ -85,11 +111,16 @@ struct Scratch {
   float* splitters;   // [Z*H*N][kNBMax] descending; entries past the row's buckets are -inf
   uint16_t* chist;    // [Z*H*N][maxch][kNBMax] bucket counts per cell of `cell` tokens
   uint32_t* coffs;    // same shape: offset of the cell inside its row
-  uint32_t* counters; // [0]=#spans [1]=#big spans [2]=error flag
-  int4* spans;        // [max_spans]  (row, begin, end, 0)
+  uint32_t* counters; // [0]=#spans [1]=#big spans [2]=error flag [3]=#rows redone by the exact path
+  uint32_t* cursor;   // [Z*H*N][kNBMax] pairs claimed so far in each bucket's region (= its population at the end)
+  uint32_t* rowflag;  // [Z*H*N] != 0: a bucket of the row outgrew its region
+  uint32_t* bst;      // [Z*H*N][kNBMax+1] rank at which each bucket of the row starts
+  int32_t* redo;      // [Z*H*N] rows whose buckets are laid out again by the exact (counting) path
+  int4* spans;        // [max_spans][2]  (row, first rank, end rank, w), (starts of the span's first four buckets)
   int4* bigspans;     // [max_spans]
   float* sk;          // [Z*H*P] s_K, used when the caller does not ask for the scores
-  uint64_t* pairs;    // [Z*H*P]
+  uint64_t* pairs;    // [Z*H][region_base(N)]: per row one region per bucket (see bucket_cap)
+  int64_t pairs_per_head;
   uint64_t* alt;      // [kBigGrid * L]
   int64_t max_spans;
   int maxch;          // cells per row
@@ -128,10 +159,15 @@ static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S, int non_ca
   s.chist = (uint16_t*)take((size_t)rows * s.maxch * kNBMax * 2);
   s.coffs = (uint32_t*)take((size_t)rows * s.maxch * kNBMax * 4);
   s.counters = (uint32_t*)take(64);
-  s.spans = (int4*)take((size_t)s.max_spans * 16);
+  s.cursor = (uint32_t*)take((size_t)rows * kNBMax * 4);
+  s.rowflag = (uint32_t*)take((size_t)rows * 4);
+  s.bst = (uint32_t*)take((size_t)rows * (kNBMax + 1) * 4);
+  s.redo = (int32_t*)take((size_t)rows * 4);
+  s.spans = (int4*)take((size_t)s.max_spans * 32);
   s.bigspans = (int4*)take((size_t)s.max_spans * 16);
   s.sk = (float*)take((size_t)Z * H * P * 4);
-  s.pairs = (uint64_t*)take((size_t)Z * H * P * 8);
+  s.pairs_per_head = region_base(N, S, L, non_causal);
+  s.pairs = (uint64_t*)take((size_t)Z * H * s.pairs_per_head * 8);
   s.alt = (uint64_t*)take((size_t)kBigGrid * L * 8);
   s.total = off;
   return s;
@@ -259,6 +295,10 @@ __global__ __launch_bounds__(256) void pool_sq_sort_kernel(PlanArgs a, Scratch s
 #pragma unroll
     for (int j = 0; j < 8; ++j) a.k_guide[((int64_t)z * a.Hkv + g) * kD + 8 * c + j] = kgv[j];
   }
+
+  // the scatter's bucket cursors of this row start at zero
+  if (tid < kNBMax) sc.cursor[row_id * kNBMax + tid] = 0u;
+  if (tid == kNBMax) sc.rowflag[row_id] = 0u;
 
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int row = r; row < a.S; row += 16) {
@@ -453,6 +493,12 @@ __device__ inline int64_t row_base(const PlanArgs& a, int64_t row_id) {
   return zh * kv_rows_total(a.N, a.S, a.L, a.non_causal) + kv_row_start(n, a.S, a.L, a.non_causal);
 }
 
+// First pair slot of a row's regions.
+__device__ inline uint64_t* row_pairs(const PlanArgs& a, const Scratch& sc, int64_t row_id) {
+  const int n = (int)(row_id % a.N);
+  return sc.pairs + (row_id / a.N) * sc.pairs_per_head + region_base(n, a.S, a.L, a.non_causal);
+}
+
 // Bucket of a score = number of the row's (descending) splitters above it.  Two levels, both
 // by counting instead of a dependent binary search: every 8th splitter sits in a register
 // (top[k] = splitter 8k+7), the group of 7 below the hit comes from LDS with two 16-byte reads.
@@ -474,20 +520,70 @@ __device__ inline int bucket_of_score(const float* spl, const float (&top)[7], f
 // dozen registers, and enough wavefronts are resident to hide the LDS round trips
 // (re-computing the scores with MFMA in these passes kept them latency-bound at a quarter
 // of the issue rate).
-__global__ __launch_bounds__(256) void count_kernel(PlanArgs a, Scratch sc) {
+// Exact path, pass 1 (only for the rows on the redo list): bucket counts per cell.
+__global__ __launch_bounds__(256) void count_kernel(PlanArgs a, Scratch sc, int64_t rows) {
   __shared__ __attribute__((aligned(16))) float spl[kNBMax];
   __shared__ uint32_t cnt[kNBMax];
+  const int64_t nredo = min((int64_t)sc.counters[3], rows);
+  for (int64_t item = blockIdx.x; item < nredo * sc.maxch; item += gridDim.x) {
+    const int64_t row_id = sc.redo[item / sc.maxch];
+    const int cellno = (int)(item % sc.maxch);
+    const int lim = (int)kv_row_len(row_id % a.N, a.S, a.L, a.non_causal);   // keys this row ranks
+    const int t_begin = cellno * sc.cell;
+    if (t_begin >= lim) continue;
+    const int t_end = min(t_begin + sc.cell, lim);
+    const int tid = threadIdx.x;
+    // four consecutive scores per thread, requested before the splitters are staged (cells and
+    // prefix lengths are multiples of 4 tokens and rows start 16-byte aligned)
+    const float* sk = (a.s_k ? a.s_k : sc.sk) + row_base(a, row_id);
+    const int t0 = t_begin + 4 * tid;
+    f32x4 sv4 = {0.f, 0.f, 0.f, 0.f};
+    if (t0 < t_end) sv4 = *reinterpret_cast<const f32x4*>(sk + t0);
+    __syncthreads();                      // the previous item's counters have been written out
+    if (tid < kNBMax) {
+      spl[tid] = sc.splitters[row_id * kNBMax + tid];
+      cnt[tid] = 0u;
+    }
+    __syncthreads();
+    float top[7];
+#pragma unroll
+    for (int k = 0; k < 7; ++k) top[k] = spl[8 * k + 7];
+    if (t0 < t_end) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) atomicAdd(&cnt[bucket_of_score(spl, top, sv4[e])], 1u);
+    }
+    __syncthreads();
+    if (tid < kNBMax) sc.chist[(row_id * sc.maxch + cellno) * kNBMax + tid] = (uint16_t)cnt[tid];
+  }
+}
+
+// Scatter: the cell's (key, token) pairs are first placed in LDS sorted by bucket (rank from an
+// LDS cursor that starts at the bucket's offset inside the cell), each with its destination;
+// the staged pairs are then written out in staged order, so that the lanes of a store
+// instruction hit runs of consecutive addresses (a bucket's run of this cell) instead of 64
+// different cache lines.
+//
+// scatter_kernel (every row): the cell counts its own buckets in LDS, claims a run for each in
+// the bucket's region with one atomic add on the row's cursor and writes there.  The order of
+// the runs inside a region depends on which workgroup claims first; the sorts that follow order
+// by (score, token), so the maps do not.  A bucket that would outgrow its region marks the row
+// for the exact path and writes nothing.
+__global__ __launch_bounds__(256) void scatter_kernel(PlanArgs a, Scratch sc) {
+  __shared__ __attribute__((aligned(16))) float spl[kNBMax];
+  __shared__ uint32_t cnt[kNBMax];              // population of each bucket in this cell
+  __shared__ uint32_t cur[kNBMax];              // next free staging slot of each bucket
+  __shared__ uint32_t delta[kNBMax];            // slot in the row's regions - staging slot; ~0: no room
+  __shared__ uint64_t stage[kCellMax];
+  __shared__ uint32_t sdst[kCellMax];
   const int64_t row_id = blockIdx.x / sc.maxch;
   const int cellno = blockIdx.x % sc.maxch;
-  const int lim = (int)kv_row_len(row_id % a.N, a.S, a.L, a.non_causal);   // keys this row ranks
+  const int lim = (int)kv_row_len(row_id % a.N, a.S, a.L, a.non_causal);
   const int t_begin = cellno * sc.cell;
   if (t_begin >= lim) return;
   const int t_end = min(t_begin + sc.cell, lim);
   const int tid = threadIdx.x;
-  // four consecutive scores per thread, requested before the splitters are staged (cells and
-  // prefix lengths are multiples of 4 tokens and rows start 16-byte aligned)
   const float* sk = (a.s_k ? a.s_k : sc.sk) + row_base(a, row_id);
-  const int t0 = t_begin + 4 * tid;
+  const int t0 = t_begin + 4 * tid;             // four consecutive scores per thread
   f32x4 sv4 = {0.f, 0.f, 0.f, 0.f};
   if (t0 < t_end) sv4 = *reinterpret_cast<const f32x4*>(sk + t0);
   if (tid < kNBMax) {
@@ -498,74 +594,118 @@ __global__ __launch_bounds__(256) void count_kernel(PlanArgs a, Scratch sc) {
   float top[7];
 #pragma unroll
   for (int k = 0; k < 7; ++k) top[k] = spl[8 * k + 7];
+  int bk[4] = {0, 0, 0, 0};
   if (t0 < t_end) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) atomicAdd(&cnt[bucket_of_score(spl, top, sv4[e])], 1u);
+    for (int e = 0; e < 4; ++e) {
+      bk[e] = bucket_of_score(spl, top, sv4[e]);
+      atomicAdd(&cnt[bk[e]], 1u);
+    }
   }
   __syncthreads();
-  if (tid < kNBMax) sc.chist[(row_id * sc.maxch + cellno) * kNBMax + tid] = (uint16_t)cnt[tid];
-}
-
-// Scatter: the cell's (key, token) pairs are first placed in LDS sorted by bucket (rank from an
-// LDS cursor that starts at the bucket's offset inside the cell), each with its destination
-// (the cell's offset in the bucket's global range + its rank); the staged pairs are then
-// written out in staged order, so that the lanes of a store instruction hit runs of
-// consecutive addresses (a bucket's run of this cell) instead of 64 different cache lines.
-__global__ __launch_bounds__(256) void scatter_kernel(PlanArgs a, Scratch sc) {
-  __shared__ __attribute__((aligned(16))) float spl[kNBMax];
-  __shared__ uint32_t cur[kNBMax];              // next free staging slot of each bucket
-  __shared__ uint32_t delta[kNBMax];            // global offset of the bucket's run - its first slot
-  __shared__ uint64_t stage[kCellMax];
-  __shared__ uint32_t sdst[kCellMax];
-  const int64_t row_id = blockIdx.x / sc.maxch;
-  const int cellno = blockIdx.x % sc.maxch;
-  const int lim = (int)kv_row_len(row_id % a.N, a.S, a.L, a.non_causal);
-  const int t_begin = cellno * sc.cell;
-  if (t_begin >= lim) return;
-  const int t_end = min(t_begin + sc.cell, lim);
-  const int tid = threadIdx.x;
-  const int64_t cell = (row_id * sc.maxch + cellno) * kNBMax;
-  const int64_t base = row_base(a, row_id);
-  const float* sk = (a.s_k ? a.s_k : sc.sk) + base;
-  const int t0 = t_begin + 4 * tid;             // four consecutive scores per thread, as in the count
-  f32x4 sv4 = {0.f, 0.f, 0.f, 0.f};
-  if (t0 < t_end) sv4 = *reinterpret_cast<const f32x4*>(sk + t0);
-  if (tid < kNBMax) {                           // one wavefront: exclusive scan of the cell's counts
-    spl[tid] = sc.splitters[row_id * kNBMax + tid];
-    const uint32_t v = sc.chist[cell + tid];
+  const uint32_t cap = bucket_cap(lim);
+  if (tid < kNBMax) {                           // one wavefront: staging offsets and the claims
+    const uint32_t v = cnt[tid];
     uint32_t incl = v;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
       const uint32_t u = __shfl_up(incl, o);
       if (tid >= o) incl += u;
     }
-    cur[tid] = incl - v;
-    delta[tid] = sc.coffs[cell + tid] - (incl - v);
+    const uint32_t excl = incl - v;
+    cur[tid] = excl;
+    uint32_t d = 0xffffffffu;
+    if (v > 0) {
+      const uint32_t at = atomicAdd(&sc.cursor[row_id * kNBMax + tid], v);
+      if (at + v <= cap) d = (uint32_t)tid * cap + at - excl;
+      else sc.rowflag[row_id] = 1u;
+    }
+    delta[tid] = d;
   }
   __syncthreads();
-  float top[7];
-#pragma unroll
-  for (int k = 0; k < 7; ++k) top[k] = spl[8 * k + 7];
   if (t0 < t_end) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const float sv = sv4[e];
-      const int bk = bucket_of_score(spl, top, sv);
-      const uint32_t slot = atomicAdd(&cur[bk], 1u);
+      const uint32_t slot = atomicAdd(&cur[bk[e]], 1u);
       if (slot < (uint32_t)kCellMax) {
-        stage[slot] = sort_key(sv, (uint32_t)(t0 + e));
-        sdst[slot] = delta[bk] + slot;
+        stage[slot] = sort_key(sv4[e], (uint32_t)(t0 + e));
+        const uint32_t d = delta[bk[e]];
+        sdst[slot] = d == 0xffffffffu ? d : d + slot;
       } else {
         raise(a, sc, 1u);
       }
     }
   }
   __syncthreads();
+  uint64_t* dstp = row_pairs(a, sc, row_id);
   const int n_here = t_end - t_begin;
   for (int i = tid; i < n_here; i += 256) {
     const uint32_t d = sdst[i];
-    if (d < (uint32_t)lim) sc.pairs[base + d] = stage[i];
-    else raise(a, sc, 8u);
+    if (d != 0xffffffffu) dstp[d] = stage[i];
+  }
+}
+
+// Exact path, pass 3 (rows on the redo list): the same staging, destinations from the counted
+// offsets; the row's pairs end up compact, in bucket order, from the start of its regions.
+__global__ __launch_bounds__(256) void scatter_exact_kernel(PlanArgs a, Scratch sc, int64_t rows) {
+  __shared__ __attribute__((aligned(16))) float spl[kNBMax];
+  __shared__ uint32_t cur[kNBMax];              // next free staging slot of each bucket
+  __shared__ uint32_t delta[kNBMax];            // global offset of the bucket's run - its first slot
+  __shared__ uint64_t stage[kCellMax];
+  __shared__ uint32_t sdst[kCellMax];
+  const int64_t nredo = min((int64_t)sc.counters[3], rows);
+  for (int64_t item = blockIdx.x; item < nredo * sc.maxch; item += gridDim.x) {
+    const int64_t row_id = sc.redo[item / sc.maxch];
+    const int cellno = (int)(item % sc.maxch);
+    const int lim = (int)kv_row_len(row_id % a.N, a.S, a.L, a.non_causal);
+    const int t_begin = cellno * sc.cell;
+    if (t_begin >= lim) continue;
+    const int t_end = min(t_begin + sc.cell, lim);
+    const int tid = threadIdx.x;
+    const int64_t cell = (row_id * sc.maxch + cellno) * kNBMax;
+    const float* sk = (a.s_k ? a.s_k : sc.sk) + row_base(a, row_id);
+    const int t0 = t_begin + 4 * tid;
+    f32x4 sv4 = {0.f, 0.f, 0.f, 0.f};
+    if (t0 < t_end) sv4 = *reinterpret_cast<const f32x4*>(sk + t0);
+    __syncthreads();                            // the previous item's staging has been written out
+    if (tid < kNBMax) {                         // one wavefront: exclusive scan of the cell's counts
+      spl[tid] = sc.splitters[row_id * kNBMax + tid];
+      const uint32_t v = sc.chist[cell + tid];
+      uint32_t incl = v;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t u = __shfl_up(incl, o);
+        if (tid >= o) incl += u;
+      }
+      cur[tid] = incl - v;
+      delta[tid] = sc.coffs[cell + tid] - (incl - v);
+    }
+    __syncthreads();
+    float top[7];
+#pragma unroll
+    for (int k = 0; k < 7; ++k) top[k] = spl[8 * k + 7];
+    if (t0 < t_end) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float sv = sv4[e];
+        const int bk = bucket_of_score(spl, top, sv);
+        const uint32_t slot = atomicAdd(&cur[bk], 1u);
+        if (slot < (uint32_t)kCellMax) {
+          stage[slot] = sort_key(sv, (uint32_t)(t0 + e));
+          sdst[slot] = delta[bk] + slot;
+        } else {
+          raise(a, sc, 1u);
+        }
+      }
+    }
+    __syncthreads();
+    uint64_t* dstp = row_pairs(a, sc, row_id);
+    const int n_here = t_end - t_begin;
+    for (int i = tid; i < n_here; i += 256) {
+      const uint32_t d = sdst[i];
+      if (d < (uint32_t)lim) dstp[d] = stage[i];
+      else raise(a, sc, 8u);
+    }
   }
 }
 
@@ -598,46 +738,43 @@ __global__ __launch_bounds__(256) void splitter_kernel(PlanArgs a, Scratch sc) {
   }
 }
 
-// Per prefix row: offsets of the (chunk, bucket) cells in bucket-major order, and the list
-// of spans handed to the sort kernels.
-__global__ __launch_bounds__(4 * kNBMax) void scan_kernel(PlanArgs a, Scratch sc) {
-  __shared__ uint32_t part[4][kNBMax];   // counts of bucket b in chunk group q
-  __shared__ uint32_t tot[kNBMax];
-  __shared__ uint32_t bstart[kNBMax + 1];
-  const int64_t row_id = blockIdx.x;
-  const int len = (int)kv_row_len(row_id % a.N, a.S, a.L, a.non_causal);
-  if (len == 0) return;
-  const int b = threadIdx.x % kNBMax, q = threadIdx.x / kNBMax;
-  const int nb = row_buckets(len);
-  const int nch = (len + sc.cell - 1) / sc.cell;
-  const int c0 = (nch * q) / 4, c1 = (nch * (q + 1)) / 4;   // this thread's chunk range
-  const uint16_t* ch = sc.chist + row_id * sc.maxch * kNBMax;
-  uint32_t* co = sc.coffs + row_id * sc.maxch * kNBMax;
-  uint32_t t = 0;
-  if (b < nb)
-    for (int c = c0; c < c1; ++c) t += ch[c * kNBMax + b];
-  part[q][b] = t;
-  __syncthreads();
-  if (q == 0) tot[b] = part[0][b] + part[1][b] + part[2][b] + part[3][b];
-  __syncthreads();
-  __shared__ int2 lspan[kNBMax + 1], lbig[kNBMax];   // this row's spans, gathered locally
-  __shared__ uint32_t nsp[2], gbase[2];
+// Span records handed to the sorts: (row, first rank, end rank, w).  w & 0xffff = first bucket
+// of the span; w & kCompact: the row's pairs lie compact in rank order from the start of its
+// regions (exact path), otherwise bucket k's pairs lie at k * bucket_cap from there and
+// sc.bst[row][k] is the rank at which bucket k starts.
+constexpr int kCompact = 0x10000;
+// w & kFewBuckets: the span lies inside its first four buckets, whose first ranks are the second
+// half of the record -- the sort then finds a pair's region without a trip to memory.
+constexpr int kFewBuckets = 0x20000;
+
+// Cuts a row's buckets (populations tot[0..nb)) into spans that fit the LDS sort and buckets
+// that do not, and appends both lists to the global ones.  Called by thread 0 .. of a
+// workgroup of at least kNBMax + 1 threads; bstart receives the ranks at which the buckets start.
+__device__ inline void emit_spans(const PlanArgs& a, const Scratch& sc, int64_t row_id, int nb, int len,
+                                  const uint32_t* tot, uint32_t* bstart, int layout, int2* lspan, int* lk0,
+                                  int2* lbig, int* lbk, uint32_t* nsp, uint32_t* gbase) {
   if (threadIdx.x == 0) {
     uint32_t off = 0, span_begin = 0, ns = 0, nbig = 0;
+    int span_k0 = 0;
     for (int k = 0; k < nb; ++k) {
       const uint32_t cnt = tot[k];
       bstart[k] = off;
       if (cnt > (uint32_t)kSpanCap) {
-        if (off > span_begin) lspan[ns++] = make_int2((int)span_begin, (int)off);
+        if (off > span_begin) { lk0[ns] = span_k0; lspan[ns++] = make_int2((int)span_begin, (int)off); }
+        lbk[nbig] = k;
         lbig[nbig++] = make_int2((int)off, (int)(off + cnt));
         span_begin = off + cnt;
+        span_k0 = k + 1;
       } else if (off + cnt - span_begin > (uint32_t)kSpanCap) {
+        lk0[ns] = span_k0;
         lspan[ns++] = make_int2((int)span_begin, (int)off);
         span_begin = off;
+        span_k0 = k;
       }
       off += cnt;
     }
-    if (off > span_begin) lspan[ns++] = make_int2((int)span_begin, (int)off);
+    bstart[nb] = off;
+    if (off > span_begin) { lk0[ns] = span_k0; lspan[ns++] = make_int2((int)span_begin, (int)off); }
     if (off != (uint32_t)len) raise(a, sc, 2u);
     nsp[0] = ns; nsp[1] = nbig;
     // one reservation per list instead of one (slow, serialised) atomic per span
@@ -646,22 +783,84 @@ __global__ __launch_bounds__(4 * kNBMax) void scan_kernel(PlanArgs a, Scratch sc
   }
   __syncthreads();
   if (threadIdx.x < nsp[0]) {
-    if ((int64_t)(gbase[0] + threadIdx.x) < sc.max_spans)
-      sc.spans[gbase[0] + threadIdx.x] = make_int4((int)row_id, lspan[threadIdx.x].x, lspan[threadIdx.x].y, 0);
-    else raise(a, sc, 4u);
+    if ((int64_t)(gbase[0] + threadIdx.x) < sc.max_spans) {
+      const int k0 = lk0[threadIdx.x];
+      const uint32_t q0 = bstart[min(k0, nb)], q1 = bstart[min(k0 + 1, nb)], q2 = bstart[min(k0 + 2, nb)],
+                     q3 = bstart[min(k0 + 3, nb)], q4 = bstart[min(k0 + 4, nb)];
+      const int few = (uint32_t)lspan[threadIdx.x].y <= q4 ? kFewBuckets : 0;
+      sc.spans[2 * (gbase[0] + threadIdx.x)] =
+          make_int4((int)row_id, lspan[threadIdx.x].x, lspan[threadIdx.x].y, k0 | layout | few);
+      sc.spans[2 * (gbase[0] + threadIdx.x) + 1] = make_int4((int)q0, (int)q1, (int)q2, (int)q3);
+    } else {
+      raise(a, sc, 4u);
+    }
   }
   if (threadIdx.x < nsp[1]) {
     if ((int64_t)(gbase[1] + threadIdx.x) < sc.max_spans)
-      sc.bigspans[gbase[1] + threadIdx.x] = make_int4((int)row_id, lbig[threadIdx.x].x, lbig[threadIdx.x].y, 0);
+      sc.bigspans[gbase[1] + threadIdx.x] =
+          make_int4((int)row_id, lbig[threadIdx.x].x, lbig[threadIdx.x].y, lbk[threadIdx.x] | layout);
     else raise(a, sc, 4u);
   }
+  if (threadIdx.x <= (unsigned)nb) sc.bst[row_id * (kNBMax + 1) + threadIdx.x] = bstart[threadIdx.x];
+}
+
+// Per prefix row, after the scatter: the bucket populations are the final cursor values; cut
+// them into spans, or put the row on the redo list if one of its buckets did not fit.
+__global__ __launch_bounds__(2 * kNBMax) void span_kernel(PlanArgs a, Scratch sc) {
+  __shared__ uint32_t tot[kNBMax];
+  __shared__ uint32_t bstart[kNBMax + 1];
+  __shared__ int2 lspan[kNBMax + 1], lbig[kNBMax];
+  __shared__ int lk0[kNBMax + 1], lbk[kNBMax];
+  __shared__ uint32_t nsp[2], gbase[2];
+  const int64_t row_id = blockIdx.x;
+  const int len = (int)kv_row_len(row_id % a.N, a.S, a.L, a.non_causal);
+  if (len == 0) return;
+  if (sc.rowflag[row_id]) {
+    if (threadIdx.x == 0) sc.redo[atomicAdd(&sc.counters[3], 1u)] = (int32_t)row_id;
+    return;
+  }
+  const int nb = row_buckets(len);
+  if (threadIdx.x < kNBMax) tot[threadIdx.x] = (int)threadIdx.x < nb ? sc.cursor[row_id * kNBMax + threadIdx.x] : 0u;
   __syncthreads();
-  if (b < nb) {
-    uint32_t running = bstart[b];
-    for (int k = 0; k < q; ++k) running += part[k][b];
-    for (int c = c0; c < c1; ++c) {
-      co[c * kNBMax + b] = running;
-      running += ch[c * kNBMax + b];
+  emit_spans(a, sc, row_id, nb, len, tot, bstart, 0, lspan, lk0, lbig, lbk, nsp, gbase);
+}
+
+// Exact path, pass 2 (rows on the redo list): offsets of the (cell, bucket) runs in
+// bucket-major order, and the row's spans.
+__global__ __launch_bounds__(4 * kNBMax) void scan_exact_kernel(PlanArgs a, Scratch sc, int64_t rows) {
+  __shared__ uint32_t part[4][kNBMax];   // counts of bucket b in chunk group q
+  __shared__ uint32_t tot[kNBMax];
+  __shared__ uint32_t bstart[kNBMax + 1];
+  __shared__ int2 lspan[kNBMax + 1], lbig[kNBMax];
+  __shared__ int lk0[kNBMax + 1], lbk[kNBMax];
+  __shared__ uint32_t nsp[2], gbase[2];
+  const int64_t nredo = min((int64_t)sc.counters[3], rows);
+  for (int64_t item = blockIdx.x; item < nredo; item += gridDim.x) {
+    const int64_t row_id = sc.redo[item];
+    const int len = (int)kv_row_len(row_id % a.N, a.S, a.L, a.non_causal);
+    const int b = threadIdx.x % kNBMax, q = threadIdx.x / kNBMax;
+    const int nb = row_buckets(len);
+    const int nch = (len + sc.cell - 1) / sc.cell;
+    const int c0 = (nch * q) / 4, c1 = (nch * (q + 1)) / 4;   // this thread's chunk range
+    const uint16_t* ch = sc.chist + row_id * sc.maxch * kNBMax;
+    uint32_t* co = sc.coffs + row_id * sc.maxch * kNBMax;
+    uint32_t t = 0;
+    if (b < nb)
+      for (int c = c0; c < c1; ++c) t += ch[c * kNBMax + b];
+    __syncthreads();                     // the previous row's tables are no longer read
+    part[q][b] = t;
+    __syncthreads();
+    if (q == 0) tot[b] = part[0][b] + part[1][b] + part[2][b] + part[3][b];
+    __syncthreads();
+    emit_spans(a, sc, row_id, nb, len, tot, bstart, kCompact, lspan, lk0, lbig, lbk, nsp, gbase);
+    __syncthreads();
+    if (b < nb) {
+      uint32_t running = bstart[b];
+      for (int k = 0; k < q; ++k) running += part[k][b];
+      for (int c = c0; c < c1; ++c) {
+        co[c * kNBMax + b] = running;
+        running += ch[c * kNBMax + b];
+      }
     }
   }
 }
@@ -685,13 +884,58 @@ __global__ __launch_bounds__(kSortThreads) void span_sort_kernel(PlanArgs a, Scr
   int4 sp = make_int4(0, 0, 0, 0);
   uint64_t held[kPerLoad];
   auto fetch = [&](uint32_t w) {
-    sp = sc.spans[w];
-    const uint64_t* src = sc.pairs + row_base(a, sp.x) + sp.y;
+    sp = sc.spans[2 * w];
+    const int4 sq = sc.spans[2 * w + 1];
+    const uint64_t* src = row_pairs(a, sc, sp.x);
     const int n = sp.z - sp.y;
+    if (sp.w & kCompact) {
 #pragma unroll
-    for (int e = 0; e < kPerLoad; ++e) {
-      const int i = tid + e * kSortThreads;
-      held[e] = i < n ? src[i] : 0ull;
+      for (int e = 0; e < kPerLoad; ++e) {
+        const int i = tid + e * kSortThreads;
+        held[e] = i < n ? src[sp.y + i] : 0ull;
+      }
+    } else {
+      // rank r of the row lies in the bucket k with bst[k] <= r < bst[k+1], at slot r - bst[k]
+      // of that bucket's region
+      const uint32_t cap = bucket_cap(kv_row_len(sp.x % a.N, a.S, a.L, a.non_causal));
+      const int k0 = sp.w & 0xffff;
+      if (sp.w & kFewBuckets) {
+        // the span's first ranks per bucket came with the record; m = buckets after the first
+        // that begin inside the span (uniform over the workgroup)
+        const uint32_t q0 = (uint32_t)sq.x, q1 = (uint32_t)sq.y, q2 = (uint32_t)sq.z, q3 = (uint32_t)sq.w;
+        const uint32_t end = (uint32_t)sp.z;
+        const int m = (q1 < end ? 1 : 0) + (q2 < end ? 1 : 0) + (q3 < end ? 1 : 0);
+        const uint32_t base0 = (uint32_t)k0 * cap - q0;
+#pragma unroll
+        for (int e = 0; e < kPerLoad; ++e) {
+          const int i = tid + e * kSortThreads;
+          uint64_t v = 0ull;
+          if (i < n) {
+            const uint32_t r = (uint32_t)(sp.y + i);
+            uint32_t off = base0;                               // region start - first rank of the bucket
+            if (m > 0 && r >= q1) off = (uint32_t)(k0 + 1) * cap - q1;
+            if (m > 1 && r >= q2) off = (uint32_t)(k0 + 2) * cap - q2;
+            if (m > 2 && r >= q3) off = (uint32_t)(k0 + 3) * cap - q3;
+            v = src[off + r];
+          }
+          held[e] = v;
+        }
+      } else {                                  // many (nearly) empty buckets in one span
+        const uint32_t* bst = sc.bst + (int64_t)sp.x * (kNBMax + 1);
+        int k = k0;
+        uint32_t b0 = bst[k], b1 = bst[k + 1];
+#pragma unroll
+        for (int e = 0; e < kPerLoad; ++e) {
+          const int i = tid + e * kSortThreads;
+          uint64_t v = 0ull;
+          if (i < n) {
+            const uint32_t r = (uint32_t)(sp.y + i);
+            while (r >= b1) { ++k; b0 = b1; b1 = bst[k + 1]; }
+            v = src[(uint32_t)k * cap + (r - b0)];
+          }
+          held[e] = v;
+        }
+      }
     }
   };
   if (blockIdx.x < nspans) fetch(blockIdx.x);
@@ -808,7 +1052,11 @@ __global__ __launch_bounds__(256) void big_sort_kernel(PlanArgs a, Scratch sc) {
     const int4 sp = sc.bigspans[w];
     const int64_t base = row_base(a, sp.x) + sp.y;
     const int len = sp.z - sp.y;
-    uint64_t* src = sc.pairs + base;
+    // the bucket's pairs: at its rank in a compact row, else at the start of its region
+    uint64_t* const home = row_pairs(a, sc, sp.x) +
+        ((sp.w & kCompact) ? (int64_t)sp.y
+                           : (int64_t)(sp.w & 0xffff) * bucket_cap(kv_row_len(sp.x % a.N, a.S, a.L, a.non_causal)));
+    uint64_t* src = home;
     uint64_t* dst = mine;
     for (int pass = 0; pass < 8; ++pass) {
       const int shift = 8 * pass;
@@ -843,7 +1091,7 @@ __global__ __launch_bounds__(256) void big_sort_kernel(PlanArgs a, Scratch sc) {
       __syncthreads();
     }
     // 8 passes: the sorted data is back in the pair scratch
-    for (int i = tid; i < len; i += 256) a.kv_perm[base + i] = (int32_t)(uint32_t)sc.pairs[base + i];
+    for (int i = tid; i < len; i += 256) a.kv_perm[base + i] = (int32_t)(uint32_t)home[i];
     __syncthreads();
   }
 }
@@ -892,9 +1140,15 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
       hipLaunchKernelGGL(splitter_kernel, dim3((unsigned)rows), dim3(256), (size_t)ns2 * 8, stream, a, sc);
     }
     const dim3 cgrid((unsigned)(rows * sc.maxch));
-    hipLaunchKernelGGL(count_kernel, cgrid, dim3(256), 0, stream, a, sc);
-    hipLaunchKernelGGL(scan_kernel, dim3((unsigned)rows), dim3(4 * kNBMax), 0, stream, a, sc);
     hipLaunchKernelGGL(scatter_kernel, cgrid, dim3(256), 0, stream, a, sc);
+    hipLaunchKernelGGL(span_kernel, dim3((unsigned)rows), dim3(2 * kNBMax), 0, stream, a, sc);
+    // the exact path for rows in which a bucket outgrew its region: normally none, and these
+    // three launches find an empty list
+    const dim3 rgrid((unsigned)(rows * sc.maxch < kRedoGrid ? rows * sc.maxch : kRedoGrid));
+    hipLaunchKernelGGL(count_kernel, rgrid, dim3(256), 0, stream, a, sc, rows);
+    hipLaunchKernelGGL(scan_exact_kernel, dim3((unsigned)(rows < kRedoGrid ? rows : kRedoGrid)), dim3(4 * kNBMax), 0,
+                       stream, a, sc, rows);
+    hipLaunchKernelGGL(scatter_exact_kernel, rgrid, dim3(256), 0, stream, a, sc, rows);
     const int64_t sort_grid = sc.max_spans < 8192 ? sc.max_spans : 8192;
     hipLaunchKernelGGL(span_sort_kernel, dim3((unsigned)sort_grid), dim3(kSortThreads), 0, stream, a, sc);
     hipLaunchKernelGGL(big_sort_kernel, dim3(kBigGrid), dim3(256), 0, stream, a, sc);

@@ -392,6 +392,24 @@ def test_degenerate_scores_take_the_fallback_sort(gpu):
         assert np.array_equal(pg["kv_perm"][0, 1, o:o + n * w.S], np.argsort(-sk, kind="stable"))
 
 
+def test_partly_tied_scores_mix_both_bucket_layouts(gpu):
+    """A block of identical keys inside otherwise continuous scores: in the rows whose prefix
+    holds the block one bucket outgrows its region, so those rows take the exact (counting)
+    layout and the tied bucket the fallback sort, while the short rows keep the fast layout;
+    every row must still be the stable argsort of its scores."""
+    w = inputs.workload("llama8k", L=16384, S=1024, H=2, Hkv=1, seed=5)
+    _say("case: partly tied scores, L=16384 S=1024")
+    Qb, Kb, Vb = inputs.make_qkv(w)
+    Kb[0, 0, 3000:9000] = Kb[0, 0, 3000]                 # 6000 equal keys: more than two average buckets
+    Qd, Kd = gu.to_dev(Qb), gu.to_dev(Kb)
+    plan, pg = gu.gpu_plan(w, Qd, Kd)
+    for h in range(2):
+        for n in range(1, w.N):
+            o = orc.kv_row_offset(n, w.S)
+            sk = pg["s_k"][0, h, o:o + n * w.S]
+            assert np.array_equal(pg["kv_perm"][0, h, o:o + n * w.S], np.argsort(-sk, kind="stable")), (h, n)
+
+
 def test_llama8k(gpu):
     """Llama-3.1-8B head shape at 8K: full plan parity on every head; attention parity on
     one query head per KV group over the threshold sweep; tau = 0 against dense."""
