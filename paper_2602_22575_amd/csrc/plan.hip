@@ -57,7 +57,11 @@ constexpr int kSubBuckets = 2048;  // fine buckets of the in-LDS sort
 constexpr int kSubMax = 64;        // a fuller sub-bucket sends the span to the bitonic fallback
 constexpr int kChunkMax = 1024;    // key tokens per score workgroup (halved while the grid is too small)
 constexpr int kCellMax = 1024;     // key tokens per (row, cell) of the bucket counts (16-bit counters)
-constexpr int kSub = 64;           // key tokens per LDS tile of the score kernel (32 in the scatter pass)
+constexpr int kSub = 64;           // key tokens per LDS tile of the score kernel
+constexpr int kScoreWaves = 4;     // wavefronts (row blocks of 32) of a score workgroup.  8 would let all 4 x 64 rows
+                                   // of a KV head at 128K share one pass over its K rows (295 against 307 us alone),
+                                   // but an 8-wavefront workgroup of 200 registers needs a whole CU at once and
+                                   // starves beside the own-segment pass on the second stream (up to 3 ms)
 constexpr int kKStride = 136;      // bf16 elements per K row in LDS (272 B)
 constexpr int kBigGrid = 64;       // workgroups of the fallback sort
 constexpr int kRedoGrid = 2048;    // workgroups of the exact path's kernels (they loop over the redo list)
@@ -139,7 +143,7 @@ static Scratch carve(void* base, int Z, int H, int Hkv, int L, int S, int non_ca
   s.max_spans = (int64_t)Z * H * (3 * P / kSpanCap + 2 * N) + 8;
   // one workgroup per (KV head, 128 rows, chunk): keep at least ~1024 of them in the grid
   {
-    const int64_t rbg = ((int64_t)(H / Hkv) * N + 127) / 128;
+    const int64_t rbg = ((int64_t)(H / Hkv) * N + 32 * kScoreWaves - 1) / (32 * kScoreWaves);
     s.chunk = kChunkMax;
     while (s.chunk > kSub && (int64_t)Z * Hkv * rbg * ((L + s.chunk - 1) / s.chunk) < 1024) s.chunk /= 2;
   }
@@ -353,17 +357,17 @@ __global__ __launch_bounds__(256) void pool_sq_sort_kernel(PlanArgs a, Scratch s
 }
 
 // ---------------------------------------------------------------------------------------
-// s_K scoring.  Workgroup = (z, g, group of 4 row blocks, chunk of sc.chunk tokens); wavefront w
-// owns row block 4*group + w (32 rows of the contraction's N side) and keeps its q_mean split
-// fragments in registers for the whole chunk; the chunk's K rows pass through LDS in tiles
-// of kSub tokens shared by the four wavefronts.  Row r of KV head g is (hq = r / N,
+// s_K scoring.  Workgroup = (z, g, group of kScoreWaves row blocks, chunk of sc.chunk tokens);
+// wavefront w owns row block kScoreWaves*group + w (32 rows of the contraction's N side) and keeps
+// its q_mean split fragments in registers for the whole chunk; the chunk's K rows pass through
+// LDS in tiles of kSub tokens shared by the wavefronts.  Row r of KV head g is (hq = r / N,
 // n = r % N) and needs tokens t < n*S.
 //   A (32 tokens x 16 dims): K tile rows from LDS, lane (token = l%32, hh = l/32) reads dims
 //                            16*kk + 8*hh .. +8
 //   B (16 dims x 32 rows)  : q_mean split terms, lane (row = l%32, hh) holds the same dims
 //   C (32 tokens x 32 rows): register i of lane l = [token 8*(i/4) + 4*hh + i%4][row l%32],
 //                            so a lane sees one row only and its meta data are scalars
-__global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
+__global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(PlanArgs a, Scratch sc) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t* Kt = reinterpret_cast<uint16_t*>(smem);                          // [kSub][kKStride]
 
@@ -389,12 +393,12 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
   const int g = unit % a.Hkv, z = unit / a.Hkv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m_ = lane & 31, hh = lane >> 5;
-  const int rb = 4 * rbg + wave;
+  const int rb = kScoreWaves * rbg + wave;
 
   auto row_limit = [&](int r) { return r < R ? (int)kv_row_len(r % a.N, a.S, a.L, a.non_causal) : 0; };
   // token limits: of the workgroup's rows (uniform) and of this wavefront's rows
   int lim_wg = 0, lim_wave = 0;
-  for (int i = 0; i < 128; ++i) lim_wg = max(lim_wg, row_limit(128 * rbg + i));
+  for (int i = 0; i < 32 * kScoreWaves; ++i) lim_wg = max(lim_wg, row_limit(32 * kScoreWaves * rbg + i));
   for (int i = 0; i < 32; ++i) lim_wave = max(lim_wave, row_limit(32 * rb + i));
   const int t_begin = chunk * sc.chunk;
   if (t_begin >= lim_wg) return;
@@ -425,18 +429,19 @@ __global__ __launch_bounds__(256) void score_kernel(PlanArgs a, Scratch sc) {
   // K tile loader: thread (c, q) moves 16-byte chunk c of rows q, q+16, ...
   const uint16_t* Kh = a.K + z * a.ks[0] + g * a.ks[1];
   const int c = tid & 15, q = tid >> 4;
-  u32x4 kreg[kSub / 16];
+  constexpr int kLoadRows = 4 * kScoreWaves;      // tile rows one pass of the loader covers
+  u32x4 kreg[kSub / kLoadRows];
   auto load_tile = [&](int t0) {
 #pragma unroll
-    for (int s = 0; s < kSub / 16; ++s) {
-      const int t = min(t0 + q + 16 * s, a.L - 1);
+    for (int s = 0; s < kSub / kLoadRows; ++s) {
+      const int t = min(t0 + q + kLoadRows * s, a.L - 1);
       kreg[s] = *reinterpret_cast<const u32x4*>(Kh + (int64_t)t * a.ks[2] + 8 * c);
     }
   };
   auto store_tile = [&]() {
 #pragma unroll
-    for (int s = 0; s < kSub / 16; ++s)
-      *reinterpret_cast<u32x4*>(Kt + (q + 16 * s) * kKStride + 8 * c) = kreg[s];
+    for (int s = 0; s < kSub / kLoadRows; ++s)
+      *reinterpret_cast<u32x4*>(Kt + (q + kLoadRows * s) * kKStride + 8 * c) = kreg[s];
   };
 
   load_tile(t_begin);
@@ -497,6 +502,15 @@ __device__ inline int64_t row_base(const PlanArgs& a, int64_t row_id) {
 __device__ inline uint64_t* row_pairs(const PlanArgs& a, const Scratch& sc, int64_t row_id) {
   const int n = (int)(row_id % a.N);
   return sc.pairs + (row_id / a.N) * sc.pairs_per_head + region_base(n, a.S, a.L, a.non_causal);
+}
+// The same two for a row given as (head index zh = z*H + h, segment n): the sorts look rows up
+// once per span and per thread, where the 64-bit divisions above would cost as much as ranking
+// a few keys.
+__device__ inline int64_t row_base(const PlanArgs& a, int zh, int n) {
+  return (int64_t)zh * kv_rows_total(a.N, a.S, a.L, a.non_causal) + kv_row_start(n, a.S, a.L, a.non_causal);
+}
+__device__ inline uint64_t* row_pairs(const PlanArgs& a, const Scratch& sc, int zh, int n) {
+  return sc.pairs + (int64_t)zh * sc.pairs_per_head + region_base(n, a.S, a.L, a.non_causal);
 }
 
 // Bucket of a score = number of the row's (descending) splitters above it.  Two levels, both
@@ -571,7 +585,7 @@ __global__ __launch_bounds__(256) void count_kernel(PlanArgs a, Scratch sc, int6
 __global__ __launch_bounds__(256) void scatter_kernel(PlanArgs a, Scratch sc) {
   __shared__ __attribute__((aligned(16))) float spl[kNBMax];
   __shared__ uint32_t cnt[kNBMax];              // population of each bucket in this cell
-  __shared__ uint32_t cur[kNBMax];              // next free staging slot of each bucket
+  __shared__ uint32_t cur[kNBMax];              // first staging slot of each bucket
   __shared__ uint32_t delta[kNBMax];            // slot in the row's regions - staging slot; ~0: no room
   __shared__ uint64_t stage[kCellMax];
   __shared__ uint32_t sdst[kCellMax];
@@ -594,12 +608,14 @@ __global__ __launch_bounds__(256) void scatter_kernel(PlanArgs a, Scratch sc) {
   float top[7];
 #pragma unroll
   for (int k = 0; k < 7; ++k) top[k] = spl[8 * k + 7];
+  // the counting atomic also ranks the pair inside its (cell, bucket) run
   int bk[4] = {0, 0, 0, 0};
+  uint32_t rk[4] = {0, 0, 0, 0};
   if (t0 < t_end) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       bk[e] = bucket_of_score(spl, top, sv4[e]);
-      atomicAdd(&cnt[bk[e]], 1u);
+      rk[e] = atomicAdd(&cnt[bk[e]], 1u);
     }
   }
   __syncthreads();
@@ -626,7 +642,7 @@ __global__ __launch_bounds__(256) void scatter_kernel(PlanArgs a, Scratch sc) {
   if (t0 < t_end) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const uint32_t slot = atomicAdd(&cur[bk[e]], 1u);
+      const uint32_t slot = cur[bk[e]] + rk[e];
       if (slot < (uint32_t)kCellMax) {
         stage[slot] = sort_key(sv4[e], (uint32_t)(t0 + e));
         const uint32_t d = delta[bk[e]];
@@ -886,7 +902,8 @@ __global__ __launch_bounds__(kSortThreads) void span_sort_kernel(PlanArgs a, Scr
   auto fetch = [&](uint32_t w) {
     sp = sc.spans[2 * w];
     const int4 sq = sc.spans[2 * w + 1];
-    const uint64_t* src = row_pairs(a, sc, sp.x);
+    const int row_n = sp.x % a.N, row_zh = sp.x / a.N;
+    const uint64_t* src = row_pairs(a, sc, row_zh, row_n);
     const int n = sp.z - sp.y;
     if (sp.w & kCompact) {
 #pragma unroll
@@ -897,7 +914,7 @@ __global__ __launch_bounds__(kSortThreads) void span_sort_kernel(PlanArgs a, Scr
     } else {
       // rank r of the row lies in the bucket k with bst[k] <= r < bst[k+1], at slot r - bst[k]
       // of that bucket's region
-      const uint32_t cap = bucket_cap(kv_row_len(sp.x % a.N, a.S, a.L, a.non_causal));
+      const uint32_t cap = bucket_cap(kv_row_len(row_n, a.S, a.L, a.non_causal));
       const int k0 = sp.w & 0xffff;
       if (sp.w & kFewBuckets) {
         // the span's first ranks per bucket came with the record; m = buckets after the first
@@ -940,7 +957,7 @@ __global__ __launch_bounds__(kSortThreads) void span_sort_kernel(PlanArgs a, Scr
   };
   if (blockIdx.x < nspans) fetch(blockIdx.x);
   for (uint32_t w = blockIdx.x; w < nspans; w += gridDim.x) {
-    const int64_t base = row_base(a, sp.x) + sp.y;
+    const int64_t base = row_base(a, sp.x / a.N, sp.x % a.N) + sp.y;
     const int len = sp.z - sp.y;
     const bool more = w + gridDim.x < nspans;
     if (tid == 0) { red[0] = 0xffffffffu; red[1] = 0u; red[2] = 0u; }
@@ -1129,10 +1146,10 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
   }
   if (a.N > 1 || a.non_causal) {
     const int RB = (G * a.N + 31) / 32;
-    const int RBG = (RB + 3) / 4;
+    const int RBG = (RB + kScoreWaves - 1) / kScoreWaves;
     const int nchunks = (a.L + sc.chunk - 1) / sc.chunk;
     const dim3 grid((unsigned)((int64_t)a.Z * a.Hkv * RBG * nchunks));
-    hipLaunchKernelGGL(score_kernel, grid, dim3(256), kScoreLds, stream, a, sc);
+    hipLaunchKernelGGL(score_kernel, grid, dim3(64 * kScoreWaves), kScoreLds, stream, a, sc);
     {
       int ns2 = 1;
       while (ns2 < a.L / kSampleStride) ns2 <<= 1;
