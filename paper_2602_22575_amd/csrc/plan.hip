@@ -57,7 +57,7 @@ constexpr int kSubBuckets = 2048;  // fine buckets of the in-LDS sort
 constexpr int kSubMax = 64;        // a fuller sub-bucket sends the span to the bitonic fallback
 constexpr int kChunkMax = 1024;    // key tokens per score workgroup (halved while the grid is too small)
 constexpr int kCellMax = 1024;     // key tokens per (row, cell) of the bucket counts (16-bit counters)
-constexpr int kSub = 64;           // key tokens per LDS tile of the score kernel
+constexpr int kSub = 128;          // key tokens per LDS tile of the score kernel
 constexpr int kScoreWaves = 4;     // wavefronts (row blocks of 32) of a score workgroup.  8 would let all 4 x 64 rows
                                    // of a KV head at 128K share one pass over its K rows (295 against 307 us alone),
                                    // but an 8-wavefront workgroup of 200 registers needs a whole CU at once and
@@ -304,24 +304,34 @@ __global__ __launch_bounds__(256) void pool_sq_sort_kernel(PlanArgs a, Scratch s
   if (tid < kNBMax) sc.cursor[row_id * kNBMax + tid] = 0u;
   if (tid == kNBMax) sc.rowflag[row_id] = 0u;
 
+  // Four rows of a thread per trip, all four 16-byte loads issued before the first is used
+  // (S is a multiple of 64: no tail).
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int row = r; row < a.S; row += 16) {
-    const u32x4 v = *reinterpret_cast<const u32x4*>(Qs + (int64_t)row * a.qs[2] + 8 * c);
-    float dot = 0.f;
+  for (int row0 = r; row0 < a.S; row0 += 64) {
+    u32x4 v4[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float x0 = bf16_lo(v[q]), x1 = bf16_hi(v[q]);
-      acc[2 * q] += x0; acc[2 * q + 1] += x1;
-      dot = fmaf(x0, kgv[2 * q], dot);
-      dot = fmaf(x1, kgv[2 * q + 1], dot);
-    }
-    dot += __shfl_xor(dot, 8);
-    dot += __shfl_xor(dot, 4);
-    dot += __shfl_xor(dot, 2);
-    dot += __shfl_xor(dot, 1);
-    if (c == 0) {
-      keys[row] = sort_key(dot, (uint32_t)row);
-      if (a.s_q) a.s_q[row_id * a.S + row] = dot;
+    for (int u = 0; u < 4; ++u)
+      v4[u] = *reinterpret_cast<const u32x4*>(Qs + (int64_t)(row0 + 16 * u) * a.qs[2] + 8 * c);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int row = row0 + 16 * u;
+      const u32x4 v = v4[u];
+      float dot = 0.f;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float x0 = bf16_lo(v[q]), x1 = bf16_hi(v[q]);
+        acc[2 * q] += x0; acc[2 * q + 1] += x1;
+        dot = fmaf(x0, kgv[2 * q], dot);
+        dot = fmaf(x1, kgv[2 * q + 1], dot);
+      }
+      dot += __shfl_xor(dot, 8);
+      dot += __shfl_xor(dot, 4);
+      dot += __shfl_xor(dot, 2);
+      dot += __shfl_xor(dot, 1);
+      if (c == 0) {
+        keys[row] = sort_key(dot, (uint32_t)row);
+        if (a.s_q) a.s_q[row_id * a.S + row] = dot;
+      }
     }
   }
   for (int i = a.S + tid; i < n2; i += 256) keys[i] = ~0ull;
