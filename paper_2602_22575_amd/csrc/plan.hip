@@ -56,7 +56,9 @@ constexpr int kSpanCap = 4096;     // elements one span_sort workgroup sorts in 
 constexpr int kSubBuckets = 2048;  // fine buckets of the in-LDS sort
 constexpr int kSubMax = 64;        // a fuller sub-bucket sends the span to the bitonic fallback
 constexpr int kChunkMax = 1024;    // key tokens per score workgroup (halved while the grid is too small)
-constexpr int kCellMax = 1024;     // key tokens per (row, cell) of the bucket counts (16-bit counters)
+constexpr int kCellMax = 1024;     // key tokens per (row, cell) of the scatter: four per thread (512 tokens and
+                                   // 128 threads: 489 against 476 us at 128K)
+constexpr int kScatterThreads = kCellMax / 4;
 constexpr int kSub = 128;          // key tokens per LDS tile of the score kernel
 constexpr int kScoreWaves = 4;     // wavefronts (row blocks of 32) of a score workgroup.  8 would let all 4 x 64 rows
                                    // of a KV head at 128K share one pass over its K rows (295 against 307 us alone),
@@ -592,24 +594,34 @@ __global__ __launch_bounds__(256) void count_kernel(PlanArgs a, Scratch sc, int6
 // the runs inside a region depends on which workgroup claims first; the sorts that follow order
 // by (score, token), so the maps do not.  A bucket that would outgrow its region marks the row
 // for the exact path and writes nothing.
-__global__ __launch_bounds__(256) void scatter_kernel(PlanArgs a, Scratch sc) {
+constexpr int kCellsPerWg = 1;     // consecutive cells of a row per scatter workgroup (a later cell's scores are
+                                   // requested before the earlier cell is worked on).  2 is slower at 128K (532
+                                   // against 476 us): the kernel lives on the number of independent workgroups
+                                   // in flight, not on the latency of one
+
+__global__ __launch_bounds__(kScatterThreads) void scatter_kernel(PlanArgs a, Scratch sc) {
   __shared__ __attribute__((aligned(16))) float spl[kNBMax];
   __shared__ uint32_t cnt[kNBMax];              // population of each bucket in this cell
   __shared__ uint32_t cur[kNBMax];              // first staging slot of each bucket
   __shared__ uint32_t delta[kNBMax];            // slot in the row's regions - staging slot; ~0: no room
   __shared__ uint64_t stage[kCellMax];
   __shared__ uint32_t sdst[kCellMax];
-  const int64_t row_id = blockIdx.x / sc.maxch;
-  const int cellno = blockIdx.x % sc.maxch;
+  const int cgroups = (sc.maxch + kCellsPerWg - 1) / kCellsPerWg;
+  const int64_t row_id = blockIdx.x / cgroups;
+  const int cell0 = (int)(blockIdx.x % cgroups) * kCellsPerWg;
   const int lim = (int)kv_row_len(row_id % a.N, a.S, a.L, a.non_causal);
-  const int t_begin = cellno * sc.cell;
-  if (t_begin >= lim) return;
-  const int t_end = min(t_begin + sc.cell, lim);
+  if (cell0 * sc.cell >= lim) return;
   const int tid = threadIdx.x;
   const float* sk = (a.s_k ? a.s_k : sc.sk) + row_base(a, row_id);
-  const int t0 = t_begin + 4 * tid;             // four consecutive scores per thread
-  f32x4 sv4 = {0.f, 0.f, 0.f, 0.f};
-  if (t0 < t_end) sv4 = *reinterpret_cast<const f32x4*>(sk + t0);
+  // four consecutive scores per thread (cells and prefix lengths are multiples of 4 tokens and
+  // rows start 16-byte aligned)
+  auto load4 = [&](int cellno) {
+    const int t = cellno * sc.cell + 4 * tid;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (t < min((cellno + 1) * sc.cell, lim)) v = *reinterpret_cast<const f32x4*>(sk + t);
+    return v;
+  };
+  f32x4 sv4 = load4(cell0);
   if (tid < kNBMax) {
     spl[tid] = sc.splitters[row_id * kNBMax + tid];
     cnt[tid] = 0u;
@@ -618,56 +630,67 @@ __global__ __launch_bounds__(256) void scatter_kernel(PlanArgs a, Scratch sc) {
   float top[7];
 #pragma unroll
   for (int k = 0; k < 7; ++k) top[k] = spl[8 * k + 7];
-  // the counting atomic also ranks the pair inside its (cell, bucket) run
-  int bk[4] = {0, 0, 0, 0};
-  uint32_t rk[4] = {0, 0, 0, 0};
-  if (t0 < t_end) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      bk[e] = bucket_of_score(spl, top, sv4[e]);
-      rk[e] = atomicAdd(&cnt[bk[e]], 1u);
-    }
-  }
-  __syncthreads();
   const uint32_t cap = bucket_cap(lim);
-  if (tid < kNBMax) {                           // one wavefront: staging offsets and the claims
-    const uint32_t v = cnt[tid];
-    uint32_t incl = v;
+  uint64_t* dstp = row_pairs(a, sc, row_id);
+  for (int ci = 0; ci < kCellsPerWg; ++ci) {
+    const int cellno = cell0 + ci;
+    const int t_begin = cellno * sc.cell;
+    if (t_begin >= lim) break;
+    const int t_end = min(t_begin + sc.cell, lim);
+    const int t0 = t_begin + 4 * tid;
+    f32x4 svn = {0.f, 0.f, 0.f, 0.f};
+    if (ci + 1 < kCellsPerWg) svn = load4(cellno + 1);
+    // the counting atomic also ranks the pair inside its (cell, bucket) run
+    int bk[4] = {0, 0, 0, 0};
+    uint32_t rk[4] = {0, 0, 0, 0};
+    if (t0 < t_end) {
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const uint32_t u = __shfl_up(incl, o);
-      if (tid >= o) incl += u;
-    }
-    const uint32_t excl = incl - v;
-    cur[tid] = excl;
-    uint32_t d = 0xffffffffu;
-    if (v > 0) {
-      const uint32_t at = atomicAdd(&sc.cursor[row_id * kNBMax + tid], v);
-      if (at + v <= cap) d = (uint32_t)tid * cap + at - excl;
-      else sc.rowflag[row_id] = 1u;
-    }
-    delta[tid] = d;
-  }
-  __syncthreads();
-  if (t0 < t_end) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const uint32_t slot = cur[bk[e]] + rk[e];
-      if (slot < (uint32_t)kCellMax) {
-        stage[slot] = sort_key(sv4[e], (uint32_t)(t0 + e));
-        const uint32_t d = delta[bk[e]];
-        sdst[slot] = d == 0xffffffffu ? d : d + slot;
-      } else {
-        raise(a, sc, 1u);
+      for (int e = 0; e < 4; ++e) {
+        bk[e] = bucket_of_score(spl, top, sv4[e]);
+        rk[e] = atomicAdd(&cnt[bk[e]], 1u);
       }
     }
-  }
-  __syncthreads();
-  uint64_t* dstp = row_pairs(a, sc, row_id);
-  const int n_here = t_end - t_begin;
-  for (int i = tid; i < n_here; i += 256) {
-    const uint32_t d = sdst[i];
-    if (d != 0xffffffffu) dstp[d] = stage[i];
+    __syncthreads();                            // also: the previous cell's staging has been written out
+    if (tid < kNBMax) {                         // one wavefront: staging offsets and the claims
+      const uint32_t v = cnt[tid];
+      cnt[tid] = 0u;                            // for the next cell
+      uint32_t incl = v;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t u = __shfl_up(incl, o);
+        if (tid >= o) incl += u;
+      }
+      const uint32_t excl = incl - v;
+      cur[tid] = excl;
+      uint32_t d = 0xffffffffu;
+      if (v > 0) {
+        const uint32_t at = atomicAdd(&sc.cursor[row_id * kNBMax + tid], v);
+        if (at + v <= cap) d = (uint32_t)tid * cap + at - excl;
+        else sc.rowflag[row_id] = 1u;
+      }
+      delta[tid] = d;
+    }
+    __syncthreads();
+    if (t0 < t_end) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t slot = cur[bk[e]] + rk[e];
+        if (slot < (uint32_t)kCellMax) {
+          stage[slot] = sort_key(sv4[e], (uint32_t)(t0 + e));
+          const uint32_t d = delta[bk[e]];
+          sdst[slot] = d == 0xffffffffu ? d : d + slot;
+        } else {
+          raise(a, sc, 1u);
+        }
+      }
+    }
+    __syncthreads();
+    const int n_here = t_end - t_begin;
+    for (int i = tid; i < n_here; i += kScatterThreads) {
+      const uint32_t d = sdst[i];
+      if (d != 0xffffffffu) dstp[d] = stage[i];
+    }
+    sv4 = svn;
   }
 }
 
@@ -1166,8 +1189,8 @@ hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
       if ((size_t)ns2 * 8 > kSplitterLdsMax) return hipErrorInvalidValue;   // unreachable: the API refuses L > 1M tokens
       hipLaunchKernelGGL(splitter_kernel, dim3((unsigned)rows), dim3(256), (size_t)ns2 * 8, stream, a, sc);
     }
-    const dim3 cgrid((unsigned)(rows * sc.maxch));
-    hipLaunchKernelGGL(scatter_kernel, cgrid, dim3(256), 0, stream, a, sc);
+    const dim3 cgrid((unsigned)(rows * ((sc.maxch + kCellsPerWg - 1) / kCellsPerWg)));
+    hipLaunchKernelGGL(scatter_kernel, cgrid, dim3(kScatterThreads), 0, stream, a, sc);
     hipLaunchKernelGGL(span_kernel, dim3((unsigned)rows), dim3(2 * kNBMax), 0, stream, a, sc);
     // the exact path for rows in which a bucket outgrew its region: normally none, and these
     // three launches find an empty list
