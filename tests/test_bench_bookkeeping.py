@@ -57,3 +57,37 @@ def test_local_tiles_match_a_brute_force_block_count(bench):
             if (t * BN) // S == (b * BM) // S and mask[b * BM:(b + 1) * BM, t * BN:(t + 1) * BN].any():
                 own += 1
     assert bench.local_tiles(_w(L, S, BM, BN)) == own
+
+
+def test_counter_traffic_is_quoted_only_for_the_sources_it_was_measured_on(bench, tmp_path, monkeypatch):
+    """A TRAFFIC line of profiles/ is returned while its src= equals the hash of the kernel
+    sources in the tree; on any other sources the figure is withheld and marked stale."""
+    here = bench.kernel_source_id()
+    assert len(here) == 12 and here == bench.kernel_source_id()
+    prof = tmp_path / "profiles"
+    prof.mkdir()
+    (prof / "a.txt").write_text(
+        "notes\n"
+        f"TRAFFIC workload=w1 tau=0.005 block_m=64 kernel=k1 bytes=123 commit=abc src={here}\n"
+        "TRAFFIC workload=w1 tau=0.005 block_m=64 kernel=k2 bytes=456 commit=abc src=000000000000\n")
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    monkeypatch.setattr(bench, "kernel_source_id", lambda: here)
+    b, src = bench.recorded_traffic("w1", 5e-3, 64, "k1")
+    assert b == 123.0 and src["stale"] is False and src["commit"] == "abc" and src["file"].endswith("a.txt")
+    b, src = bench.recorded_traffic("w1", 5e-3, 64, "k2")
+    assert b is None and src["stale"] is True
+    assert bench.recorded_traffic("w1", 5e-3, 128, "k1") == (None, None)
+    assert bench.recorded_traffic("w1", 1e-3, 64, "k1") == (None, None)
+
+
+def test_tracked_traffic_lines_match_the_sources_in_the_tree(bench):
+    """The figures bench.py would quote today: every TRAFFIC line on file names the current
+    kernel sources (a kernel change without a fresh counter run shows up here, not in a stale
+    roofline.traffic)."""
+    import glob
+    here = bench.kernel_source_id()
+    lines = [l for f in glob.glob(os.path.join(ROOT, "profiles", "*.txt")) for l in open(f) if l.startswith("TRAFFIC ")]
+    assert lines
+    stale = [l for l in lines if f"src={here}" not in l]
+    if stale:
+        pytest.skip(f"{len(stale)} TRAFFIC line(s) were measured on other kernel sources; bench.py reports them as stale")
