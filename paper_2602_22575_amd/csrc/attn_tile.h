@@ -446,6 +446,37 @@ __device__ __forceinline__ TileStats softmax_tile(f32x16 (&s)[2], float c2, floa
   return t;
 }
 
+// The common tile of a ranked walk raises no row's maximum by much, and then the reference does
+// not move: the numerators can be formed against the current reference straight away, without
+// the pass that finds the tile's maximum first (17 instructions and a cross-lane exchange that
+// the exponentials would have to wait for).  Whether that was admissible shows in the mass
+// itself: a numerator is at most the mass, so a mass of at most kMassLimit bounds every bf16
+// P value and every accumulator term by it.  `redo` (a larger mass, an overflow to infinity, or
+// a row that has no reference yet) tells the caller to score the tile again and take
+// softmax_tile.
+constexpr float kMassLimit = 65536.0f;
+__device__ __forceinline__ TileStats softmax_tile_keep_reference(f32x16 (&s)[2], float c2, float m_ref, float l_run,
+                                                                 bool& redo) {
+  TileStats t;
+  t.grow = false;
+  t.m_use = m_ref;
+  t.alpha = 1.0f;
+  t.prev = l_run;
+  const float neg = -m_ref;
+  float sum = 0.f;
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float pe = __builtin_amdgcn_exp2f(fmaf(s[nb][i], c2, neg));
+      s[nb][i] = pe;
+      sum += pe;
+    }
+  t.mass = xhalf_sum(sum);
+  redo = !(t.mass <= kMassLimit);
+  return t;
+}
+
 // P^T fragments (bf16) for the four 16-key contraction steps
 __device__ __forceinline__ void pack_p(const f32x16 (&s)[2], bf16x8 (&pb)[4]) {
 #pragma unroll

@@ -33,9 +33,18 @@ constexpr size_t kPrefixLds = (size_t)(4 * kTileBytes) + 64 + 4 * kWaves * 64;  
 
 template <int P> using Par = std::integral_constant<int, P>;
 
+// min(max(x, 0), hi) in one instruction (the compiler emits two: it cannot know that hi >= 0)
+__device__ __forceinline__ uint32_t clamp_token(int x, int hi) {
+  int r;
+  asm("v_med3_i32 %0, %1, 0, %2" : "=v"(r) : "v"(x), "s"(hi));
+  return (uint32_t)r;
+}
+
 // kNoStop: stop_mode 2 (every prefix tile folded in, the paper's kernel C) as an instantiation
 // of its own, so that neither loop's registers weigh on the other.
-template <bool kNoStop>
+// kMapped: the walk follows a KV_perm row (always, except the non-causal walk in storage order,
+// which then does not carry the map's registers and selects).
+template <bool kNoStop, bool kMapped>
 __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs a) {
   extern __shared__ __attribute__((aligned(256))) unsigned char smem[];   // OperandAddr needs a 256-byte base
   uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
@@ -90,17 +99,20 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   auto ring_slot = [&](int t) { return ring + (t & 3) * (16 * kWaves) + 16 * wave; };
   const int ring_row = 16 * wave + 4 * (lane & 3) + ((lane >> 2) & 3);     // row whose entry lane l < 16 requests
   auto fetch_index = [&](int t) {       // map entries of tile t (clamped tile number) -> ring; ntiles > 0
-    if (a.kv_perm && lane < 16) {
-      const int32_t* tile_idx = kvrow + (int64_t)min(t, ntiles - 1) * kBN;
-      __builtin_amdgcn_global_load_lds((const gvoid*)(tile_idx + ring_row), (lvoid*)ring_slot(t), 4, 0, 0);
+    if (kMapped && lane < 16) {
+      // scalar base + 32-bit lane offset: no 64-bit per-lane pointer is kept across the walk
+      const char* tile_idx = reinterpret_cast<const char*>(kvrow + (int64_t)min(t, ntiles - 1) * kBN);
+      asm volatile("" : "+s"(tile_idx));      // (opaque: otherwise base + lane offset is hoisted as a per-lane pointer)
+      __builtin_amdgcn_global_load_lds((const gvoid*)(tile_idx + (uint64_t)(uint32_t)(4 * ring_row)), (lvoid*)ring_slot(t),
+                                       4, 0, 0);
     }
   };
   auto tokens = [&](int t, uint32_t (&tok)[4]) {   // this lane's four tokens of tile t, clamped to the sequence
-    if (a.kv_perm) {
+    if (kMapped) {
       const int4 e = *reinterpret_cast<const int4*>(ring_slot(t) + 4 * (lane >> 4));
       const int ev[4] = {e.x, e.y, e.z, e.w};
 #pragma unroll
-      for (int gi = 0; gi < 4; ++gi) tok[gi] = (uint32_t)min(max(ev[gi], 0), a.L - 1);
+      for (int gi = 0; gi < 4; ++gi) tok[gi] = clamp_token(ev[gi], a.L - 1);
     } else {                            // no map (non-causal only): the keys in storage order
 #pragma unroll
       for (int gi = 0; gi < 4; ++gi)
@@ -288,7 +300,12 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
         rescale(o, alpha_pend, grow_pend);
         pv_tile_sched<0, true>(fa, pb_pend, o, vfr);
         ++committed;
-        softmax();
+        bool redo;
+        ts = softmax_tile_keep_reference(s, c2, m_ref, l_run, redo);
+        if (__builtin_amdgcn_ballot_w64(redo) != 0ull) {   // rare: the tile moves some row's reference
+          qk_tile_only<0>(fa, qf, s);
+          softmax();
+        }
         publish(it_);
         wait_tile_loads();
         __syncthreads();
@@ -338,8 +355,10 @@ hipError_t launch_prefix(const AttnArgs& a, hipStream_t stream) {
   static std::mutex mu;
   static uint64_t done = 0;
   const hipError_t se = once_per_device(mu, done, [] {
-    const void* fns[2] = {reinterpret_cast<const void*>(&s2o_prefix_kernel<false>),
-                          reinterpret_cast<const void*>(&s2o_prefix_kernel<true>)};
+    const void* fns[4] = {reinterpret_cast<const void*>(&s2o_prefix_kernel<false, true>),
+                          reinterpret_cast<const void*>(&s2o_prefix_kernel<true, true>),
+                          reinterpret_cast<const void*>(&s2o_prefix_kernel<false, false>),
+                          reinterpret_cast<const void*>(&s2o_prefix_kernel<true, false>)};
     for (const void* f : fns) {
       const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPrefixLds);
       if (e != hipSuccess) return e;
@@ -352,10 +371,14 @@ hipError_t launch_prefix(const AttnArgs& a, hipStream_t stream) {
   const int JG = (TJ + tpw - 1) / tpw;
   const int64_t blocks = (int64_t)a.Z * a.H * a.N * JG;
   if (blocks <= 0 || blocks > 0x7fffffff) return hipErrorInvalidValue;
-  if (a.stop_mode == 2)
-    hipLaunchKernelGGL(s2o_prefix_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), kPrefixLds, stream, a);
-  else
-    hipLaunchKernelGGL(s2o_prefix_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), kPrefixLds, stream, a);
+  const dim3 grid((unsigned)blocks), block(kThreads);
+  if (a.kv_perm) {
+    if (a.stop_mode == 2) hipLaunchKernelGGL((s2o_prefix_kernel<true, true>), grid, block, kPrefixLds, stream, a);
+    else hipLaunchKernelGGL((s2o_prefix_kernel<false, true>), grid, block, kPrefixLds, stream, a);
+  } else {
+    if (a.stop_mode == 2) hipLaunchKernelGGL((s2o_prefix_kernel<true, false>), grid, block, kPrefixLds, stream, a);
+    else hipLaunchKernelGGL((s2o_prefix_kernel<false, false>), grid, block, kPrefixLds, stream, a);
+  }
   return hipGetLastError();
 }
 
