@@ -97,14 +97,18 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
 #pragma unroll
   for (int gi = 0; gi < 4; ++gi) goff[gi] = (uint32_t)load_chunk_offset(lane, 16 * wave + 4 * gi);
   auto ring_slot = [&](int t) { return ring + (t & 3) * (16 * kWaves) + 16 * wave; };
-  const int ring_row = 16 * wave + 4 * (lane & 3) + ((lane >> 2) & 3);     // row whose entry lane l < 16 requests
+  // (lane l < 16 requests the entry of tile row 16*wave + 4*(l%4) + l/4)
   auto fetch_index = [&](int t) {       // map entries of tile t (clamped tile number) -> ring; ntiles > 0
     if (kMapped && lane < 16) {
       // scalar base + 32-bit lane offset: no 64-bit per-lane pointer is kept across the walk
+      // The lane's offset is worked out again at every call (opaque lane id): kept across the
+      // walk it would be a 64-bit per-lane pointer, two registers that the allocator spills
+      // and reloads inside the step, behind a wait for every fetch in flight.
+      int l = lane;
+      asm volatile("" : "+v"(l));
+      const uint32_t row4 = (uint32_t)(4 * (16 * wave + 4 * (l & 3) + ((l >> 2) & 3)));
       const char* tile_idx = reinterpret_cast<const char*>(kvrow + (int64_t)min(t, ntiles - 1) * kBN);
-      asm volatile("" : "+s"(tile_idx));      // (opaque: otherwise base + lane offset is hoisted as a per-lane pointer)
-      __builtin_amdgcn_global_load_lds((const gvoid*)(tile_idx + (uint64_t)(uint32_t)(4 * ring_row)), (lvoid*)ring_slot(t),
-                                       4, 0, 0);
+      __builtin_amdgcn_global_load_lds((const gvoid*)(tile_idx + (uint64_t)row4), (lvoid*)ring_slot(t), 4, 0, 0);
     }
   };
   auto tokens = [&](int t, uint32_t (&tok)[4]) {   // this lane's four tokens of tile t, clamped to the sequence
@@ -211,16 +215,22 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
     pack_p(s, pb_pend);
     ++issued;
   };
-  auto tile_votes = [&](const int* vf) {
-    int votes = 0;
-    for (int p2 = 0; p2 < wpt; ++p2) votes |= vf[tile_l + tpw * p2];
-    return votes;
-  };
-  auto wg_votes = [&](const int* vf) {
-    int any = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) any |= vf[w];
-    return any;
+  // the four wavefronts' votes of a step come with one 16-byte read; a query tile's wavefronts
+  // are tile_l, tile_l + tpw, ...
+  struct Votes { int mine, any; };
+  // (The read sits in a loop of one trip whose count the compiler cannot see.  Without an inner
+  // loop in the step, the step loop is the innermost one, the compiler hoists and schedules far
+  // more aggressively, and the walk ends up with 256 registers and spill reloads -- each behind
+  // a wait for all fetches in flight -- inside the step: 158 against 110 ms for the dense walk.)
+  const int one_trip = 1 + (a.BM >> 12);
+  auto read_votes = [&](int step) {
+    Votes v = {0, 0};
+    for (int trip = 0; trip < one_trip; ++trip) {
+      const int4 f = *reinterpret_cast<const int4*>(vote_flags(step) + 4 * trip);
+      v.any |= __builtin_amdgcn_readfirstlane(f.x | f.y | f.z | f.w);
+      v.mine |= tpw == 2 ? __builtin_amdgcn_readfirstlane(tile_l == 0 ? (f.x | f.z) : (f.y | f.w)) : v.any;
+    }
+    return v;
   };
   auto end_step = [&] {                 // this wavefront's fetches have landed; everyone's after the barrier
     wait_tile_loads();
@@ -278,11 +288,11 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
         for (int db = 0; db < 4; ++db) fa.v[db] = oa.v[db] + vb;
       };
       auto step = [&](int it_) -> bool {
-        const int* vf = vote_flags(it_ - 1);
-        const int votes = tile_votes(vf);
+        const Votes vf = read_votes(it_ - 1);
+        const int votes = vf.mine;
         aim(it_);
         if (votes == 0) {
-          const int any = wg_votes(vf);
+          const int any = vf.any;
           if (a.stop_mode == 0) {
             l_run = l_save; m_ref = m_save;
           } else {
@@ -314,7 +324,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
       for (it = 1; it < ntiles; ++it)
         if (!step(it)) break;
       if (pending) {                            // the last tile: its vote is visible now
-        const bool stop = tile_votes(vote_flags(ntiles - 1)) == 0;
+        const bool stop = read_votes(ntiles - 1).mine == 0;
         if (stop && a.stop_mode == 0) {
           l_run = l_save; m_ref = m_save;
         } else {
@@ -329,7 +339,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
     // ---- drain: keep the tile pipeline fed until every query tile of the workgroup has stopped
     if (!wg_done) {
       for (; it < ntiles; ++it) {
-        if (it > 0 && wg_votes(vote_flags(it - 1)) == 0) break;
+        if (it > 0 && read_votes(it - 1).any == 0) break;
         fetch_step(it);
         if (lane == 0) vote_flags(it)[wave] = 0;
         end_step();
