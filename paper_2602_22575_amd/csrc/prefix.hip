@@ -138,16 +138,20 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
                        vd + (16 * wave + 4 * gi) * kRowElems);
   };
   // the fetches of step t (top of the step): K(t+1), V(t) (no stop rule: V(t+1)), indices of tile t+2
+  // A wavefront calls fetch_step for t = 0, 1, 2, ... in turn (working or draining), so the
+  // tokens of tile t, which V(t) needs, are the ones the previous call worked out for K(t):
+  // they stay in four registers instead of being read from the ring and clamped again.
+  uint32_t tok_cur[4] = {0, 0, 0, 0};
   auto fetch_step = [&](int t) {
     uint32_t tn[4];
     tokens(t + 1, tn);
     if (kNoStop) {
       if (t + 1 < ntiles) { load_k(t + 1, tn); load_v(t + 1, tn); }
     } else {
-      uint32_t tc[4];
-      tokens(t, tc);
       if (t + 1 < ntiles) load_k(t + 1, tn);
-      load_v(t, tc);
+      load_v(t, tok_cur);
+#pragma unroll
+      for (int gi = 0; gi < 4; ++gi) tok_cur[gi] = tn[gi];
     }
     fetch_index(t + 2);
   };
@@ -155,10 +159,9 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
     fetch_index(0);
     fetch_index(1);
     wait_tile_loads();
-    uint32_t t0[4];
-    tokens(0, t0);
-    load_k(0, t0);
-    if (kNoStop) load_v(0, t0);
+    tokens(0, tok_cur);
+    load_k(0, tok_cur);
+    if (kNoStop) load_v(0, tok_cur);
   }
 
   // ---- the query row of this lane and its Q fragments
