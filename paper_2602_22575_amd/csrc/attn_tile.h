@@ -250,12 +250,24 @@ __device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcn
 struct OperandAddr {
   uint32_t k0;        // K operand of contraction step 0, key block 0 (block 1: + 32 rows)
   uint32_t v[4];      // V^T operand: [32-dim block], keys 0..7 of a 16-key step (next step: + 16 rows)
+  uint32_t vx[4];     // v[db] ^ 16: keys 8..15 of the step sit 8 rows on from there (saves an XOR per read)
   __device__ __forceinline__ void init(int lane, uint32_t base) {
     Operands op;
     op.init(lane);
     k0 = base + 2u * (uint32_t)op.koff[0];
 #pragma unroll
-    for (int db = 0; db < 4; ++db) v[db] = base + 2u * (uint32_t)op.voff[db][0];
+    for (int db = 0; db < 4; ++db) {
+      v[db] = base + 2u * (uint32_t)op.voff[db][0];
+      vx[db] = v[db] ^ 16u;
+    }
+  }
+  // the same fragments in a tile kb / vb bytes further on (multiples of 32)
+  __device__ __forceinline__ OperandAddr at(uint32_t kb, uint32_t vb) const {
+    OperandAddr r;
+    r.k0 = k0 + kb;
+#pragma unroll
+    for (int db = 0; db < 4; ++db) { r.v[db] = v[db] + vb; r.vx[db] = vx[db] + vb; }
+    return r;
   }
 };
 
@@ -284,7 +296,7 @@ constexpr int issued_at_qk(int kk, bool with_v) {
 template <int kVOff, int c>
 __device__ __forceinline__ void issue_v_fragment(const OperandAddr& oa, u32x2 (&vf)[16][2]) {
   lds_issue_tr64_x<kVOff + (c / 4) * kVStepBytes, 0>(vf[c][0], oa.v[c % 4]);
-  lds_issue_tr64_x<kVOff + (c / 4) * kVStepBytes + 8 * kRowElems * 2, 16>(vf[c][1], oa.v[c % 4]);
+  lds_issue_tr64_x<kVOff + (c / 4) * kVStepBytes + 8 * kRowElems * 2, 0>(vf[c][1], oa.vx[c % 4]);
 }
 
 // S^T = K Q^T for the K tile at byte offset kKOff from the addresses in `oa`.  kWithV: also

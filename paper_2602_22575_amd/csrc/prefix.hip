@@ -286,9 +286,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
       auto aim = [&](int it_) {               // fa <- buffers of step it_
         const uint32_t kb = (uint32_t)(kKBytes0 + (it_ & 1) * kTileBytes);
         const uint32_t vb = (uint32_t)(kVBytes0 + ((it_ - 1) & 1) * kTileBytes);
-        fa.k0 = oa.k0 + kb;
-#pragma unroll
-        for (int db = 0; db < 4; ++db) fa.v[db] = oa.v[db] + vb;
+        fa = oa.at(kb, vb);
       };
       auto step = [&](int it_) -> bool {
         const Votes vf = read_votes(it_ - 1);
