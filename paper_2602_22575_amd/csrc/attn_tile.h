@@ -244,29 +244,35 @@ __device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcn
 
 // Byte addresses of a lane's operand fragments inside a tile that starts at LDS address `base`
 // (a multiple of 256).  The swizzle is an XOR on the 16-byte chunk index, i.e. on address bits
-// 4..7, so the eight K slots and the second V half follow from one register each by an XOR
-// with a constant (one VALU instruction at the point of use instead of a register held
-// through the kernel): K step kk = k0 ^ (kk << 5); V half 1 = (v[db] ^ 16) + 8 rows.
+// 4..7, so the eight K slots and the second V half follow from one address each by an XOR
+// with a constant: K step kk = k[0] ^ (kk << 5); V half 1 = (v[db] ^ 16) + 8 rows.  All sixteen
+// are kept: an XOR at the point of use sits between the read and the MFMA that waits for it
+// (12 XORs fewer per key tile for the V halves alone were worth 2 % of the walk).
 struct OperandAddr {
-  uint32_t k0;        // K operand of contraction step 0, key block 0 (block 1: + 32 rows)
+  uint32_t k[8];      // K operand of contraction step kk, key block 0 (block 1: + 32 rows)
   uint32_t v[4];      // V^T operand: [32-dim block], keys 0..7 of a 16-key step (next step: + 16 rows)
   uint32_t vx[4];     // v[db] ^ 16: keys 8..15 of the step sit 8 rows on from there (saves an XOR per read)
   __device__ __forceinline__ void init(int lane, uint32_t base) {
     Operands op;
     op.init(lane);
-    k0 = base + 2u * (uint32_t)op.koff[0];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) k[kk] = (base + 2u * (uint32_t)op.koff[0]) ^ (uint32_t)(kk << 5);
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
       v[db] = base + 2u * (uint32_t)op.voff[db][0];
       vx[db] = v[db] ^ 16u;
     }
   }
-  // the same fragments in a tile kb / vb bytes further on (multiples of 32)
-  __device__ __forceinline__ OperandAddr at(uint32_t kb, uint32_t vb) const {
-    OperandAddr r;
-    r.k0 = k0 + kb;
+  // the same fragments in a tile kb / vb bytes further on (multiples of 256; may be "negative")
+  __device__ __forceinline__ void shift(uint32_t kb, uint32_t vb) {
 #pragma unroll
-    for (int db = 0; db < 4; ++db) { r.v[db] = v[db] + vb; r.vx[db] = vx[db] + vb; }
+    for (int kk = 0; kk < 8; ++kk) k[kk] += kb;
+#pragma unroll
+    for (int db = 0; db < 4; ++db) { v[db] += vb; vx[db] += vb; }
+  }
+  __device__ __forceinline__ OperandAddr at(uint32_t kb, uint32_t vb) const {
+    OperandAddr r = *this;
+    r.shift(kb, vb);
     return r;
   }
 };
@@ -312,7 +318,7 @@ __device__ __forceinline__ void qk_tile_sched(const OperandAddr& oa, const bf16x
   bf16x8 ka[8][2];
   static_for<0, kKAhead>([&](auto kk_) {
     constexpr int kk = decltype(kk_)::value;
-    lds_issue_b128_x2<kKOff, (kk << 5)>(ka[kk][0], ka[kk][1], oa.k0);
+    lds_issue_b128_x2<kKOff, 0>(ka[kk][0], ka[kk][1], oa.k[kk]);
   });
   pre();
   static_for<0, 8>([&](auto kk_) {
@@ -329,7 +335,7 @@ __device__ __forceinline__ void qk_tile_sched(const OperandAddr& oa, const bf16x
       s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk][1], qf[kk], s[1], 0, 0, 0);
     }
     if constexpr (kk + kKAhead < 8) {
-      lds_issue_b128_x2<kKOff, ((kk + kKAhead) << 5)>(ka[kk + kKAhead][0], ka[kk + kKAhead][1], oa.k0);
+      lds_issue_b128_x2<kKOff, 0>(ka[kk + kKAhead][0], ka[kk + kKAhead][1], oa.k[kk + kKAhead]);
     } else if constexpr (kWithV) {
       issue_v_fragment<kVOff, 2 * (kk + kKAhead - 8)>(oa, vf);
       issue_v_fragment<kVOff, 2 * (kk + kKAhead - 8) + 1>(oa, vf);

@@ -278,20 +278,15 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
       end_step();
       bool pending = true;                      // a scored tile waits for its vote
       // One step.  K(it) sits in K buffer it & 1, V(it-1) in V buffer (it-1) & 1: the operand
-      // addresses `fa` carry the current buffers (five additions per step), so one loop body
-      // serves both parities -- two bodies with the buffer as a constant get the accumulator
-      // different registers and pay a 32-move shuffle between them on every step.
+      // addresses `fa` carry the current buffers and are moved to the other buffers at the end of
+      // every completed step (sixteen additions, outside the sequence of reads and MFMAs), so one
+      // loop body serves both parities -- two bodies with the buffer as a constant get the
+      // accumulator different registers and pay a 32-move shuffle between them on every step.
       // Returns false when the query tile stops at this step.
-      OperandAddr fa;
-      auto aim = [&](int it_) {               // fa <- buffers of step it_
-        const uint32_t kb = (uint32_t)(kKBytes0 + (it_ & 1) * kTileBytes);
-        const uint32_t vb = (uint32_t)(kVBytes0 + ((it_ - 1) & 1) * kTileBytes);
-        fa = oa.at(kb, vb);
-      };
+      OperandAddr fa = oa.at((uint32_t)(kKBytes0 + kTileBytes), (uint32_t)kVBytes0);   // step 1
       auto step = [&](int it_) -> bool {
         const Votes vf = read_votes(it_ - 1);
         const int votes = vf.mine;
-        aim(it_);
         if (votes == 0) {
           const int any = vf.any;
           if (a.stop_mode == 0) {
@@ -318,6 +313,10 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
           softmax();
         }
         publish(it_);
+        {                                       // step it_ + 1: K moves to the other buffer, V the other way
+          const uint32_t dk = (it_ & 1) ? (uint32_t)(-kTileBytes) : (uint32_t)kTileBytes;
+          fa.shift(dk, 0u - dk);
+        }
         wait_tile_loads();
         __syncthreads();
         return true;
@@ -330,8 +329,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
           l_run = l_save; m_ref = m_save;
         } else {
           rescale(o, alpha_pend, grow_pend);
-          aim(ntiles);                          // V(ntiles-1)
-          pv_tile_only<0>(fa, pb_pend, o);
+          pv_tile_only<0>(fa, pb_pend, o);      // fa stands at step ntiles: V(ntiles-1)
           ++committed;
         }
         wg_done = true;
