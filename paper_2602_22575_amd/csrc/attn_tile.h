@@ -241,6 +241,9 @@ template <int kYounger>
 __device__ __forceinline__ void lds_wait(uint32_t& a) { asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(kYounger)); }
 // All global->LDS tile loads (and every other global load) of this wavefront have landed.
 __device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// ... all but the kYoungest most recent vector-memory instructions of the wavefront (they complete in order)
+template <int kYoungest>
+__device__ __forceinline__ void wait_older_loads() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kYoungest) : "memory"); }
 
 // Byte addresses of a lane's operand fragments inside a tile that starts at LDS address `base`
 // (a multiple of 256).  The swizzle is an XOR on the 16-byte chunk index, i.e. on address bits
@@ -530,15 +533,63 @@ __device__ __forceinline__ void zero_acc(f32x16 (&o)[4]) {
     for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
 }
 
-// State buffers: a row's accumulator is kept as 128 fp32 in the accumulator's register order
-// (a lane's 16 values of a 32-dim block contiguous; `sp` = row base + 64*hh).
-__device__ __forceinline__ void store_acc(float* sp, const f32x16 (&o)[4]) {
+// State buffers: a row's accumulator is kept as 128 fp32 = four 128-byte lines, one per 32-dim
+// block db: the 16 values of the lane with hh = 0 in register order, then those of hh = 1
+// (`sp` in load_acc = row base + 16*hh).
+//
+// lines_from_acc regroups the accumulators of a wavefront's 32 consecutive rows through two
+// wavefront-private 4 KB LDS areas: afterwards lane L holds in o[db][4k .. 4k+3] the 16-byte
+// piece L % 8 of line db of row 8k + L / 8, and a store instruction of store_acc_lines writes 8
+// whole lines.  Stored straight from the accumulator layout an instruction would put 16 bytes
+// into each of 64 lines: the same bytes in 16 times as many write requests, which is what the
+// own-segment pass then waits for.  (LDS serves a wavefront's accesses in order: the reads
+// behind the writes need no wait of their own.)
+__device__ __forceinline__ void lines_from_acc(f32x16 (&o)[4], uint32_t area0, uint32_t area1, int lane) {
+  // LDS accesses in assembly, like the fragment reads: the compiler would put a wait for every
+  // outstanding global load in front of them (it cannot tell them from a global->LDS load's target)
+  const int m_ = lane & 31, hh = lane >> 5, grp = lane >> 3, piece = lane & 7;
+  const uint32_t wr = (uint32_t)(m_ * 128), rd = (uint32_t)(grp * 128 + ((piece ^ grp) << 4));
+  uint32_t wq[4];                              // pieces rotated per row: no bank conflicts
+#pragma unroll
+  for (int q = 0; q < 4; ++q) wq[q] = wr + (uint32_t)(((hh * 4 + q) ^ (m_ & 7)) << 4);
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int db = 2 * pass + half;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 v = {o[db][4 * q], o[db][4 * q + 1], o[db][4 * q + 2], o[db][4 * q + 3]};
+        asm volatile("ds_write_b128 %0, %1" :: "v"((half ? area1 : area0) + wq[q]), "v"(v) : "memory");
+      }
+    }
+    f32x4 r[2][4];
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        asm volatile("ds_read_b128 %0, %1" : "=v"(r[half][k]) : "v"((half ? area1 : area0) + rd + 1024u * k) : "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(r[0][0]), "+v"(r[0][1]), "+v"(r[0][2]), "+v"(r[0][3]), "+v"(r[1][0]), "+v"(r[1][1]),
+                   "+v"(r[1][2]), "+v"(r[1][3])
+                 :: "memory");
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[2 * pass + half][4 * k + e] = r[half][k][e];
+  }
+}
+// `wave_rows` = the accumulator state of the wavefront's first row; o as left by lines_from_acc.
+__device__ __forceinline__ void store_acc_lines(float* wave_rows, const f32x16 (&o)[4], int lane) {
+  float* p = wave_rows + (lane >> 3) * kD + (lane & 7) * 4;
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-      const f32x4 v = {o[db][4 * i4], o[db][4 * i4 + 1], o[db][4 * i4 + 2], o[db][4 * i4 + 3]};
-      *reinterpret_cast<f32x4*>(sp + 16 * db + 4 * i4) = v;
+    for (int k = 0; k < 4; ++k) {
+      const f32x4 v = {o[db][4 * k], o[db][4 * k + 1], o[db][4 * k + 2], o[db][4 * k + 3]};
+      *reinterpret_cast<f32x4*>(p + 8 * k * kD + 32 * db) = v;
     }
 }
 __device__ __forceinline__ void load_acc(const float* sp, f32x16 (&o)[4]) {
@@ -546,7 +597,7 @@ __device__ __forceinline__ void load_acc(const float* sp, f32x16 (&o)[4]) {
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int i4 = 0; i4 < 4; ++i4) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(sp + 16 * db + 4 * i4);
+      const f32x4 v = *reinterpret_cast<const f32x4*>(sp + 32 * db + 4 * i4);
       o[db][4 * i4] = v[0]; o[db][4 * i4 + 1] = v[1]; o[db][4 * i4 + 2] = v[2]; o[db][4 * i4 + 3] = v[3];
     }
 }

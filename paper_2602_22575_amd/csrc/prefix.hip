@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   float m_ref = -INFINITY, l_run = 0.f;
   if (!a.non_causal) { m_ref = a.st_m[st_row]; l_run = a.st_l[st_row]; }
   f32x16 o[4];
-  const float* st_acc_row = a.st_acc + st_row * kD + 64 * hh;
+  const float* st_acc_row = a.st_acc + st_row * kD + 16 * hh;
   auto init_acc = [&] {
     if (a.non_causal) zero_acc(o);
     else load_acc(st_acc_row, o);

@@ -48,7 +48,7 @@ struct AttnArgs {
   int32_t* computed;
   int32_t* skipped;
   int passes;     // 0: one fused launch; bit 0: Alg. 2 into the state buffers; bit 1: Alg. 3 from them
-  float* st_acc;  // state buffers: acc [Z*H*L][128], then l and m [Z*H*L]
+  float* st_acc;  // state buffers: acc [Z*H*L][128] (four 128-byte lines per row, see attn_tile.h), then l and m [Z*H*L]
   float* st_l;
   float* st_m;
   int Z, H, Hkv, L, S, N;
