@@ -602,6 +602,35 @@ __device__ __forceinline__ void load_acc(const float* sp, f32x16 (&o)[4]) {
     }
 }
 
+// Normalise a wavefront's 32 output rows and store them as whole rows: the rows are regrouped
+// through a wavefront-private 8 KB LDS area (32 rows x 256 bytes, the 16-byte chunks of a row
+// rotated by the row number against bank conflicts), so that a store instruction writes 4
+// complete rows (8 lines) where the accumulator layout would give 16 bytes to each of 32
+// lines.  `tok` = the lane's destination row (a token index, the same in both lanes of a
+// row); `head` + tok * row_stride is its address.
+__device__ __forceinline__ void store_o_rows(uint16_t* head, int64_t row_stride, int tok, unsigned char* area,
+                                             int lane, const f32x16 (&o)[4], float inv) {
+  const int n = lane & 31, hh = lane >> 5;
+  unsigned char* wr = area + n * 256 + 8 * hh;
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {            // dims 32*db + 8*i4 + 4*hh + (0..3)
+      u32x2 w;
+      w.x = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
+      w.y = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
+      *reinterpret_cast<u32x2*>(wr + (((4 * db + i4) ^ (n & 15)) << 4)) = w;
+    }
+  const int sub = lane >> 4, chunk = lane & 15;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int row = 4 * k + sub;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(area + row * 256 + ((chunk ^ (row & 15)) << 4));
+    const int t = __builtin_amdgcn_ds_bpermute(4 * row, tok);
+    *reinterpret_cast<u32x4*>(head + (int64_t)t * row_stride + 8 * chunk) = v;
+  }
+}
+
 // Normalise and store a lane's share of its output row: dims 32*db + 8*(i/4) + 4*hh + i%4.
 __device__ __forceinline__ void store_o(uint16_t* orow, int hh, const f32x16 (&o)[4], float inv) {
 #pragma unroll

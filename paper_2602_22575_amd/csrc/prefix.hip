@@ -349,7 +349,8 @@ __global__ __launch_bounds__(kThreads, 2) void s2o_prefix_kernel(const AttnArgs 
   if (active) {
     if (!acc_loaded) init_acc();                 // no prefix tile was walked (first segment)
     // normalise and scatter to the original row
-    store_o(Oh + (int64_t)(nS + qoff) * a.os[2], hh, o, 1.0f / l_run);
+    // (every wavefront of the workgroup is past the last barrier: the K buffers are idle)
+    store_o_rows(Oh, a.os[2], nS + qoff, smem + wave * 8192, lane, o, 1.0f / l_run);
     if (lane == 0 && part == 0) {
       const int64_t ci = zh * (a.L / BM) + (int64_t)n * TJ + j;
       if (a.computed) a.computed[ci] = committed;
