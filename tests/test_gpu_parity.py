@@ -347,10 +347,13 @@ def test_map_validation_switch(tiny, monkeypatch):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("L,S,H,Hkv", [(256, 256, 1, 1), (128, 64, 2, 1), (1536, 192, 4, 2), (2048, 1024, 2, 2)])
+@pytest.mark.parametrize("L,S,H,Hkv", [(256, 256, 1, 1), (128, 64, 2, 1), (1536, 192, 4, 2), (2048, 1024, 2, 2),
+                                        (1280, 320, 2, 1)])
 def test_edge_shapes(gpu, L, S, H, Hkv):
     """Single segment (no prefix at all), a one-tile segment (three idle wavefronts), a
-    segment length that is not a power of two, GQA groups."""
+    segment length that is not a power of two, GQA groups, a segment of an odd number of
+    128-row blocks whose last block is half empty (the own-segment pass pairs row blocks: the
+    middle one stands alone, and a wavefront without rows in a block carries no state out of it)."""
     w = inputs.workload("llama8k", L=L, S=S, H=H, Hkv=Hkv, seed=3)
     _say(f"case: edge shape L={L} S={S} H={H} Hkv={Hkv}")
     Qb, Kb, Vb = inputs.make_qkv(w)
