@@ -31,7 +31,8 @@
       in, identical instruction stream) on the workload's Gaussian data, with V zeroed, and with
       Q, K and V all zero, with the shader clock the driver reports sampled meanwhile: equal
       time x clock products with very different clocks mean the cycle count is fixed and the
-      clock is what the data's switching activity leaves of the power budget.
+      clock is what the data's switching activity leaves of the power budget.  Followed by the
+      own-segment pass on the workload's data and on zeros.
 
 Inputs are the seeded synthetic workloads of inputs.py; every figure is the mean of a few
 launches timed with events on the launch stream.
@@ -310,6 +311,32 @@ def power():
         th.join()
         mhz = float(np.median(samples)) if samples else float("nan")
         print(f"| {name} | {ms:.2f} | {dense_flops / (ms * 1e-3) / 1e12:.0f} | {mhz:.0f} | {ms * mhz / 1e3:.1f} |", flush=True)
+
+    # the own-segment pass the same way: 60 launches back to back per row (a single launch of
+    # 2.5 ms is too short for the clock to settle)
+    tq = w.S // w.BN
+    local_flops = 4.0 * w.BN * w.BN * w.D * (tq * (tq + 1) // 2) * w.N * w.Z * w.H   # 64x64 tiles on or below the diagonal
+    print()
+    print(f"workload {w.name}: own-segment pass, 60 launches back to back")
+    print("| data | ms per launch | TFLOP/s (64x64 tiles on or below the diagonal, counted whole) |")
+    print("|---|---|---|")
+
+    def burst(q_, k_, v_, n=60):
+        for _ in range(5):
+            s2o.s2o_attention_local(q_, k_, v_, p, scratch=state)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            s2o.s2o_attention_local(q_, k_, v_, p, scratch=state)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+    for name, (q_, k_, v_) in (("Gaussian Q, K, V (the workload)", (Qd, Kd, Vd)),
+                               ("Q = K = V = 0", (zero(Qd), zero(Kd), zero(Vd))),
+                               ("Gaussian Q, K, V again", (Qd, Kd, Vd))):
+        ms = burst(q_, k_, v_)
+        print(f"| {name} | {ms:.3f} | {local_flops / (ms * 1e-3) / 1e12:.0f} |", flush=True)
 
 
 if __name__ == "__main__":
