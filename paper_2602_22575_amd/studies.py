@@ -312,31 +312,43 @@ def power():
         mhz = float(np.median(samples)) if samples else float("nan")
         print(f"| {name} | {ms:.2f} | {dense_flops / (ms * 1e-3) / 1e12:.0f} | {mhz:.0f} | {ms * mhz / 1e3:.1f} |", flush=True)
 
-    # the own-segment pass the same way: 60 launches back to back per row (a single launch of
-    # 2.5 ms is too short for the clock to settle)
+    # the own-segment pass the same way: 120 launches back to back per row (a single launch of
+    # 2.5 ms is too short for the clock to settle, or to be sampled)
     tq = w.S // w.BN
     local_flops = 4.0 * w.BN * w.BN * w.D * (tq * (tq + 1) // 2) * w.N * w.Z * w.H   # 64x64 tiles on or below the diagonal
     print()
-    print(f"workload {w.name}: own-segment pass, 60 launches back to back")
-    print("| data | ms per launch | TFLOP/s (64x64 tiles on or below the diagonal, counted whole) |")
-    print("|---|---|---|")
+    print(f"workload {w.name}: own-segment pass, 120 launches back to back")
+    print("| data | ms per launch | TFLOP/s (64x64 tiles on or below the diagonal, counted whole) | shader clock MHz | ms x GHz |")
+    print("|---|---|---|---|---|")
 
-    def burst(q_, k_, v_, n=60):
+    def burst(q_, k_, v_, n=120):
         for _ in range(5):
             s2o.s2o_attention_local(q_, k_, v_, p, scratch=state)
         torch.cuda.synchronize()
+        samples, stop = [], [False]
+
+        def loop():
+            while not stop[0]:
+                v = sclk() if files else None
+                if v:
+                    samples.append(v)
+                time.sleep(0.002)
+        th = threading.Thread(target=loop)
+        th.start()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for _ in range(n):
             s2o.s2o_attention_local(q_, k_, v_, p, scratch=state)
         b.record()
         torch.cuda.synchronize()
-        return a.elapsed_time(b) / n
+        stop[0] = True
+        th.join()
+        return a.elapsed_time(b) / n, (float(np.median(samples)) if samples else float("nan"))
     for name, (q_, k_, v_) in (("Gaussian Q, K, V (the workload)", (Qd, Kd, Vd)),
                                ("Q = K = V = 0", (zero(Qd), zero(Kd), zero(Vd))),
                                ("Gaussian Q, K, V again", (Qd, Kd, Vd))):
-        ms = burst(q_, k_, v_)
-        print(f"| {name} | {ms:.3f} | {local_flops / (ms * 1e-3) / 1e12:.0f} |", flush=True)
+        ms, mhz = burst(q_, k_, v_)
+        print(f"| {name} | {ms:.3f} | {local_flops / (ms * 1e-3) / 1e12:.0f} | {mhz:.0f} | {ms * mhz / 1e3:.2f} |", flush=True)
 
 
 if __name__ == "__main__":
